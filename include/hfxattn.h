@@ -1,0 +1,186 @@
+/*
+ * libhfxattn -- mixed prefill/decode attention over a block-paged bf16 KV cache,
+ * for one scheduled serving step, on one AMD MI355X (gfx950).
+ *
+ * The operation behind this interface is the device work of one engine step as
+ * HFX (arXiv 2508.15919) frames it: Section 2.1 names the two phases of a step
+ * (prompt processing with full-sequence attention, compute bound; token
+ * generation over cached KV states, memory-bandwidth bound), Section 3.3.1
+ * fixes what a scheduler hands down for a step (which requests run, and how
+ * many new tokens each contributes under the token budget), and Sections
+ * 3.3.3 / 3.4 state that the KV cache is managed in fixed-size blocks.  The
+ * paper does not define the attention operator further; the result computed
+ * here is textbook scaled-dot-product attention with a causal mask and
+ * grouped-query head sharing, defined precisely at hfx_mixed_paged_attention.
+ *
+ * C ABI only: plain pointers and sizes.  Every pointer argument is tagged
+ * [host] or [device] below.  The library never allocates or frees memory that
+ * outlives a call and never synchronises a stream.  No function throws or
+ * aborts; every failure is a negative hfx_status and, when it is a validation
+ * failure, nothing has been enqueued on the stream.
+ */
+#ifndef HFXATTN_H
+#define HFXATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t hfx_status;
+
+enum {
+  HFX_OK = 0,
+  HFX_ERR_NULL = -1,     /* a required pointer is NULL                                  */
+  HFX_ERR_SHAPE = -2,    /* hfx_shape is inconsistent or unsupported                    */
+  HFX_ERR_KIND = -3,     /* kind[r] is neither HFX_DECODE nor HFX_PREFILL               */
+  HFX_ERR_LEN = -4,      /* q_len / ctx_len violate 1 <= q_len <= ctx_len (decode: q=1) */
+  HFX_ERR_PAGES = -5,    /* block table malformed or too short for ctx_len              */
+  HFX_ERR_PAGE_ID = -6,  /* a page id needed by some request is outside [0, num_pages)  */
+  HFX_ERR_BUFSIZE = -7,  /* a caller-provided buffer is too small                       */
+  HFX_ERR_DEVICE = -8,   /* the HIP runtime reported an error                           */
+  HFX_ERR_DESC = -9,     /* the descriptor blob is not one this library version wrote   */
+  HFX_ERR_ALIGN = -10    /* a device pointer is not 16-byte aligned                     */
+};
+
+/* Request kinds of a scheduled step (Section 3.3.1: in-flight decoding requests
+ * versus newly admitted requests whose prompt tokens are processed). */
+enum { HFX_DECODE = 0, HFX_PREFILL = 1 };
+
+/* Shape constants of one attention layer and its page pool. */
+typedef struct {
+  int32_t num_q_heads;   /* Hq;  Hq % Hkv == 0, group size G = Hq/Hkv <= 16               */
+  int32_t num_kv_heads;  /* Hkv; 1, 2, or a multiple of 4                                 */
+  int32_t head_dim;      /* D in {64, 128}                                                */
+  int32_t page_size;     /* tokens per KV block; must be 16                               */
+  int32_t num_pages;     /* physical pages in the pool                                    */
+  float softmax_scale;   /* multiplier of q.k before softmax; <= 0 selects 1/sqrt(D)      */
+} hfx_shape;
+
+/*
+ * KV page pool layout (bf16, one device allocation, 16-byte aligned):
+ *
+ *   pool[num_pages][Hkv][2][16 * D]
+ *
+ * For page P and kv-head g the first 16*D elements are the keys, token-major:
+ * K[slot][d] at (slot * D + d).  The second 16*D elements are the values,
+ * dimension-major: V[slot][d] at (d * 16 + slot).  Logical token t of a
+ * request lives in page bt_pages[bt_indptr[r] + t / 16] at slot t % 16
+ * (block-managed cache, Sections 3.3.3 and 3.4).  Slots at or past ctx_len in
+ * a request's last page, and pages no block table names, may hold anything
+ * (including NaN) and never influence a result.
+ */
+
+/* Human-readable name of a status code.  Returns a static string. */
+const char* hfx_status_string(hfx_status status);
+
+/* Library version.  Either pointer may be NULL. [host] */
+hfx_status hfx_version(int32_t* major, int32_t* minor);
+
+/*
+ * Sizes, in bytes, of the three caller-owned buffers a step needs.  Pure host
+ * integer work; touches no device.
+ *   host_desc_bytes        staging buffer for hfx_build_batch_desc (pinned memory
+ *                          makes the upload asynchronous; pageable also works)
+ *   device_desc_bytes      device buffer that receives the descriptor
+ *   device_workspace_bytes device scratch for split partial results (may be 0)
+ * kind, q_len, ctx_len: [host] arrays of num_requests entries, as below.
+ * Errors: HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_KIND, HFX_ERR_LEN.
+ */
+hfx_status hfx_batch_desc_sizes(const hfx_shape* shape, int32_t num_requests,
+                                const int32_t* kind, const int32_t* q_len,
+                                const int32_t* ctx_len, size_t* host_desc_bytes,
+                                size_t* device_desc_bytes,
+                                size_t* device_workspace_bytes);
+
+/*
+ * Turns the scheduler's statement of a step (Section 3.3.1: the admitted
+ * requests and the number of new tokens each contributes, next to the
+ * in-flight decodes) into the device-side batch descriptor: validated
+ * per-request records, the block table, and the cost-ordered list of work
+ * items (decode ranges, prefill tiles, split/merge groups) one launch drains.
+ * Integer work only.
+ *
+ *   kind       [host][R]   HFX_DECODE or HFX_PREFILL
+ *   q_len      [host][R]   query-chunk length; exactly 1 for HFX_DECODE
+ *   ctx_len    [host][R]   KV tokens visible to the chunk's last query,
+ *                          the chunk's own tokens included; >= q_len
+ *   bt_indptr  [host][R+1] CSR offsets into bt_pages, bt_indptr[0] == 0,
+ *                          non-decreasing; request r owns at least
+ *                          ceil(ctx_len[r]/16) entries (extra ones are ignored)
+ *   bt_pages   [host]      physical page ids in logical order; the ones a
+ *                          request needs must lie in [0, num_pages).  Two
+ *                          requests may name the same page (shared prefix).
+ *   host_desc  [host]      staging memory, host_desc_bytes as reported above
+ *   device_desc [device]   receives the descriptor, 16-byte aligned
+ *   stream                 hipStream_t (NULL = default stream)
+ *
+ * The descriptor is written into host_desc and one asynchronous host-to-device
+ * copy of it is enqueued on `stream`; host_desc must stay untouched until that
+ * copy has completed.  The five input arrays are consumed before return.  The
+ * descriptor is position independent (offsets, no pointers) and holds a few
+ * control words that launches use and restore to zero, so one descriptor may
+ * serve any number of launches (e.g. every layer of a step) as long as they
+ * do not overlap in time.
+ * Errors: every code above; nothing is enqueued unless HFX_OK is returned.
+ */
+hfx_status hfx_build_batch_desc(const hfx_shape* shape, int32_t num_requests,
+                                const int32_t* kind, const int32_t* q_len,
+                                const int32_t* ctx_len, const int32_t* bt_indptr,
+                                const int32_t* bt_pages, void* host_desc,
+                                size_t host_desc_bytes, void* device_desc,
+                                size_t device_desc_bytes, void* stream);
+
+/*
+ * Executes the attention of one scheduled step in a single persistent launch.
+ *
+ * With T = sum of q_len, requests packed in order (request r owns query rows
+ * [sum_{s<r} q_len[s], +q_len[r])):
+ *   q    [device] bf16 [T][Hq][D]
+ *   out  [device] bf16 [T][Hq][D]
+ * For request r, chunk row i (0 <= i < q_len[r]) and q-head h, let
+ * g = h / (Hq/Hkv), n = ctx_len[r] - q_len[r] + i + 1 (the causal horizon; the
+ * whole context for a decode), k_j / v_j the key / value of logical token j
+ * and kv-head g fetched through the block table.  Then
+ *   s_j = softmax_scale * <q, k_j>,  j in [0, n)
+ *   out = sum_j softmax(s)_j * v_j
+ * (Section 2.1: full-sequence attention for the prompt phase, attention over
+ * cached KV states for the generation phase.)  Scores, softmax and the
+ * weighted sum accumulate in fp32 (softmax weights are rounded to bf16 for the
+ * second contraction); the result is rounded to bf16 nearest-even.
+ *
+ *   host_desc      [host]   the staging buffer hfx_build_batch_desc filled; only
+ *                           its header is read (launch geometry), on the host
+ *   device_desc    [device] descriptor uploaded by hfx_build_batch_desc
+ *   workspace      [device] device_workspace_bytes of scratch, 16-byte aligned;
+ *                           contents need no initialisation; may be NULL when 0
+ *
+ * Asynchronous on `stream`; allocates nothing and synchronises nothing.
+ * Errors: HFX_ERR_NULL, HFX_ERR_SHAPE (shape differs from the descriptor's),
+ * HFX_ERR_DESC, HFX_ERR_BUFSIZE, HFX_ERR_ALIGN, HFX_ERR_DEVICE.
+ */
+hfx_status hfx_mixed_paged_attention(const hfx_shape* shape, const void* q,
+                                     const void* kv_pool, const void* host_desc,
+                                     void* device_desc, void* workspace,
+                                     size_t workspace_bytes, void* out,
+                                     void* stream);
+
+/*
+ * Paging check hook: copies the keys and values of request `request`, tokens
+ * [0, ctx_len), all kv-heads, out of the page pool into token-major contiguous
+ * buffers, walking the same device descriptor the attention kernel walks
+ * (block-managed KV cache, Sections 3.3.3 and 3.4).  A pure byte copy.
+ *   k_out, v_out [device] bf16 [ctx_len][Hkv][D] each
+ * Errors: HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_DESC, HFX_ERR_LEN (request out of
+ * range), HFX_ERR_DEVICE.
+ */
+hfx_status hfx_gather_kv(const hfx_shape* shape, const void* kv_pool,
+                         const void* host_desc, const void* device_desc,
+                         int32_t request, void* k_out, void* v_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HFXATTN_H */
