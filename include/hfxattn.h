@@ -134,6 +134,19 @@ hfx_status hfx_build_batch_desc(const hfx_shape* shape, int32_t num_requests,
                                 size_t device_desc_bytes, void* stream);
 
 /*
+ * The host half of hfx_build_batch_desc alone: validates and writes the
+ * descriptor into host_desc, touching no device and no stream.  For callers
+ * that upload the blob themselves (total size: host_desc_bytes as reported by
+ * hfx_batch_desc_sizes) -- e.g. as a copy node of their own.  Same inputs,
+ * same errors except HFX_ERR_DEVICE / HFX_ERR_ALIGN.
+ */
+hfx_status hfx_fill_batch_desc(const hfx_shape* shape, int32_t num_requests,
+                               const int32_t* kind, const int32_t* q_len,
+                               const int32_t* ctx_len, const int32_t* bt_indptr,
+                               const int32_t* bt_pages, void* host_desc,
+                               size_t host_desc_bytes);
+
+/*
  * Executes the attention of one scheduled step in a single persistent launch.
  *
  * With T = sum of q_len, requests packed in order (request r owns query rows

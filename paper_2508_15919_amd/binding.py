@@ -1,0 +1,260 @@
+"""Thin ctypes binding of libhfxattn's C ABI (include/hfxattn.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP kernels.
+PyTorch appears here solely as the owner of device memory and streams.  There is no CPU
+fallback: if the library has not been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhfxattn.so")
+
+HFX_OK = 0
+HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_KIND, HFX_ERR_LEN, HFX_ERR_PAGES = -1, -2, -3, -4, -5
+HFX_ERR_PAGE_ID, HFX_ERR_BUFSIZE, HFX_ERR_DEVICE, HFX_ERR_DESC, HFX_ERR_ALIGN = -6, -7, -8, -9, -10
+HFX_DECODE, HFX_PREFILL = 0, 1
+
+EXPORTS = ["hfx_status_string", "hfx_version", "hfx_batch_desc_sizes", "hfx_build_batch_desc",
+           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv"]
+
+
+class hfx_shape(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_pages", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class HfxError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {hfx_status_string(code)} ({code})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library; raises if it is missing (build it with paper_2508_15919_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2508_15919_amd.build` "
+                               "(hipcc, gfx950).  There is no fallback path.")
+        lib = ctypes.CDLL(LIB_PATH)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        szp = ctypes.POINTER(ctypes.c_size_t)
+        shp = ctypes.POINTER(hfx_shape)
+        vp = ctypes.c_void_p
+        lib.hfx_status_string.argtypes = [ctypes.c_int32]
+        lib.hfx_status_string.restype = ctypes.c_char_p
+        lib.hfx_version.argtypes = [i32p, i32p]
+        lib.hfx_version.restype = ctypes.c_int32
+        lib.hfx_batch_desc_sizes.argtypes = [shp, ctypes.c_int32, i32p, i32p, i32p, szp, szp, szp]
+        lib.hfx_batch_desc_sizes.restype = ctypes.c_int32
+        lib.hfx_fill_batch_desc.argtypes = [shp, ctypes.c_int32, i32p, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t]
+        lib.hfx_fill_batch_desc.restype = ctypes.c_int32
+        lib.hfx_build_batch_desc.argtypes = [shp, ctypes.c_int32, i32p, i32p, i32p, i32p, i32p, vp,
+                                             ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        lib.hfx_build_batch_desc.restype = ctypes.c_int32
+        lib.hfx_mixed_paged_attention.argtypes = [shp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.hfx_mixed_paged_attention.restype = ctypes.c_int32
+        lib.hfx_gather_kv.argtypes = [shp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
+        lib.hfx_gather_kv.restype = ctypes.c_int32
+        _lib = lib
+    return _lib
+
+
+def _i32(a):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _ptr(x):
+    """Raw address of a torch tensor, numpy array, int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if hasattr(x, "data_ptr"):
+        return ctypes.c_void_p(x.data_ptr())
+    if isinstance(x, np.ndarray):
+        return ctypes.c_void_p(x.ctypes.data)
+    raise TypeError(f"cannot take the address of {type(x)}")
+
+
+def _nbytes(x) -> int:
+    if x is None:
+        return 0
+    if hasattr(x, "element_size"):
+        return x.numel() * x.element_size()
+    return int(x.nbytes)
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_shape(num_q_heads, num_kv_heads, head_dim, num_pages, softmax_scale=0.0, page_size=16) -> hfx_shape:
+    return hfx_shape(int(num_q_heads), int(num_kv_heads), int(head_dim), int(page_size), int(num_pages),
+                     float(softmax_scale))
+
+
+def hfx_status_string(code: int) -> str:
+    return load().hfx_status_string(int(code)).decode()
+
+
+def hfx_version():
+    a, b = ctypes.c_int32(), ctypes.c_int32()
+    load().hfx_version(ctypes.byref(a), ctypes.byref(b))
+    return a.value, b.value
+
+
+def hfx_batch_desc_sizes(shape: hfx_shape, kind, q_len, ctx_len):
+    """Returns (host_desc_bytes, device_desc_bytes, device_workspace_bytes)."""
+    k, pk = _i32(kind)
+    q, pq = _i32(q_len)
+    c, pc = _i32(ctx_len)
+    h, d, w = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    rc = load().hfx_batch_desc_sizes(ctypes.byref(shape), len(k), pk, pq, pc, ctypes.byref(h), ctypes.byref(d),
+                                     ctypes.byref(w))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_batch_desc_sizes")
+    return h.value, d.value, w.value
+
+
+def hfx_fill_batch_desc(shape: hfx_shape, kind, q_len, ctx_len, bt_indptr, bt_pages, host_desc) -> None:
+    k, pk = _i32(kind)
+    q, pq = _i32(q_len)
+    c, pc = _i32(ctx_len)
+    bi, pbi = _i32(bt_indptr)
+    bp, pbp = _i32(bt_pages)
+    rc = load().hfx_fill_batch_desc(ctypes.byref(shape), len(k), pk, pq, pc, pbi, pbp, _ptr(host_desc),
+                                    _nbytes(host_desc))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_fill_batch_desc")
+
+
+def hfx_build_batch_desc(shape: hfx_shape, kind, q_len, ctx_len, bt_indptr, bt_pages, host_desc, device_desc,
+                         stream=None) -> None:
+    k, pk = _i32(kind)
+    q, pq = _i32(q_len)
+    c, pc = _i32(ctx_len)
+    bi, pbi = _i32(bt_indptr)
+    bp, pbp = _i32(bt_pages)
+    rc = load().hfx_build_batch_desc(ctypes.byref(shape), len(k), pk, pq, pc, pbi, pbp, _ptr(host_desc),
+                                     _nbytes(host_desc), _ptr(device_desc), _nbytes(device_desc), _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_build_batch_desc")
+
+
+def hfx_mixed_paged_attention(shape: hfx_shape, q, kv_pool, host_desc, device_desc, workspace, out,
+                              stream=None) -> None:
+    rc = load().hfx_mixed_paged_attention(ctypes.byref(shape), _ptr(q), _ptr(kv_pool), _ptr(host_desc),
+                                          _ptr(device_desc), _ptr(workspace), _nbytes(workspace), _ptr(out),
+                                          _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_mixed_paged_attention")
+
+
+def hfx_gather_kv(shape: hfx_shape, kv_pool, host_desc, device_desc, request: int, k_out, v_out,
+                  stream=None) -> None:
+    rc = load().hfx_gather_kv(ctypes.byref(shape), _ptr(kv_pool), _ptr(host_desc), _ptr(device_desc),
+                              int(request), _ptr(k_out), _ptr(v_out), _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_gather_kv")
+
+
+# ------------------------------------------------------------------------------------------
+# Read-only views of a descriptor blob, for inspection and for the planner's CPU tests.
+# They mirror csrc/hfx_desc.h.
+# ------------------------------------------------------------------------------------------
+class DescHeader(ctypes.Structure):
+    _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
+                ("num_requests", ctypes.c_int32), ("total_q", ctypes.c_int32),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("n_items", ctypes.c_int32), ("n_decode_items", ctypes.c_int32),
+                ("n_prefill_items", ctypes.c_int32), ("n_groups", ctypes.c_int32),
+                ("n_partial_rows", ctypes.c_int32), ("n_bt", ctypes.c_int32),
+                ("off_ctrl", ctypes.c_uint32), ("off_req", ctypes.c_uint32), ("off_bt", ctypes.c_uint32),
+                ("off_items", ctypes.c_uint32), ("off_groups", ctypes.c_uint32), ("n_ctrl", ctypes.c_uint32),
+                ("total_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
+                ("ws_off_ml", ctypes.c_uint64), ("reserved", ctypes.c_uint32 * 8)]
+
+
+ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
+                                               "kb", "ke", "cost", "pad")])
+REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
+                                              "pad0", "pad1")])
+GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "pad")])
+
+
+def parse_desc(host_desc: np.ndarray) -> dict:
+    """Decodes a host descriptor blob (uint8 numpy array) into header, requests, block table, items, groups."""
+    buf = np.ascontiguousarray(host_desc).view(np.uint8)
+    h = DescHeader.from_buffer_copy(buf[:ctypes.sizeof(DescHeader)].tobytes())
+    return {
+        "header": h,
+        "ctrl": buf[h.off_ctrl:h.off_ctrl + 4 * h.n_ctrl].view(np.int32),
+        "reqs": buf[h.off_req:h.off_req + REQ_DTYPE.itemsize * h.num_requests].view(REQ_DTYPE),
+        "bt": buf[h.off_bt:h.off_bt + 4 * h.n_bt].view(np.int32),
+        "items": buf[h.off_items:h.off_items + ITEM_DTYPE.itemsize * h.n_items].view(ITEM_DTYPE),
+        "groups": buf[h.off_groups:h.off_groups + GROUP_DTYPE.itemsize * h.n_groups].view(GROUP_DTYPE),
+    }
+
+
+# ------------------------------------------------------------------------------------------
+# Device-memory plumbing for callers that hold a step as numpy arrays (tests, bench, smoke).
+# ------------------------------------------------------------------------------------------
+class DeviceStep:
+    """Owns the torch buffers of one step: descriptor (pinned host + device), workspace, Q, out."""
+
+    def __init__(self, batch, pool_dev=None, device="cuda:0", softmax_scale=0.0, stream=None):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.shape = make_shape(batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.num_pages,
+                                softmax_scale)
+        hb, db, wb = hfx_batch_desc_sizes(self.shape, batch.kind, batch.q_len, batch.ctx_len)
+        self.host_desc = torch.empty(hb, dtype=torch.uint8, pin_memory=True)
+        self.device_desc = torch.empty(db, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(max(wb, 16), dtype=torch.uint8, device=self.device)
+        self.workspace_bytes = wb
+        self.pool = pool_dev if pool_dev is not None else torch.from_numpy(batch.pool.view(np.int16)).to(self.device)
+        self.q = torch.from_numpy(batch.q.view(np.int16)).to(self.device)
+        self.out = torch.zeros_like(self.q)
+        hfx_build_batch_desc(self.shape, batch.kind, batch.q_len, batch.ctx_len, batch.bt_indptr, batch.bt_pages,
+                             self.host_desc, self.device_desc, stream if stream is not None
+                             else torch.cuda.current_stream(self.device))
+        self.batch = batch
+
+    def run(self, stream=None):
+        s = stream if stream is not None else self.torch.cuda.current_stream(self.device)
+        hfx_mixed_paged_attention(self.shape, self.q, self.pool, self.host_desc, self.device_desc,
+                                  self.workspace if self.workspace_bytes else None, self.out, s)
+        return self.out
+
+    def out_bits(self) -> np.ndarray:
+        self.torch.cuda.synchronize(self.device)
+        return self.out.cpu().numpy().view(np.uint16)
+
+    def gather(self, request: int):
+        t = self.torch
+        c = int(self.batch.ctx_len[request])
+        k = t.zeros((c, self.batch.num_kv_heads, self.batch.head_dim), dtype=t.int16, device=self.device)
+        v = t.zeros_like(k)
+        hfx_gather_kv(self.shape, self.pool, self.host_desc, self.device_desc, request, k, v,
+                      t.cuda.current_stream(self.device))
+        t.cuda.synchronize(self.device)
+        return k.cpu().numpy().view(np.uint16), v.cpu().numpy().view(np.uint16)

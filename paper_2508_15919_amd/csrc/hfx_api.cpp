@@ -1,0 +1,155 @@
+// C ABI of libhfxattn (see include/hfxattn.h): argument checking, descriptor upload, launches.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+
+#include "../../include/hfxattn.h"
+#include "hfx_desc.h"
+#include "hfx_launch.h"
+#include "hfx_plan.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// header of a descriptor this library wrote, matching `shape`
+hfx_status check_header(const hfx_shape* shape, const void* host_desc, HfxHeader* out) {
+  hfx_status st = hfx::check_shape(shape);
+  if (st != HFX_OK) return st;
+  if (!host_desc) return HFX_ERR_NULL;
+  std::memcpy(out, host_desc, sizeof(HfxHeader));
+  if (out->magic != HFX_DESC_MAGIC || out->version != HFX_DESC_VERSION) return HFX_ERR_DESC;
+  if (out->num_q_heads != shape->num_q_heads || out->num_kv_heads != shape->num_kv_heads ||
+      out->head_dim != shape->head_dim || out->page_size != shape->page_size ||
+      out->num_pages != shape->num_pages)
+    return HFX_ERR_SHAPE;
+  return HFX_OK;
+}
+
+// resident workgroups of the persistent kernel on the current device, cached per device
+hfx_status persistent_grid(int head_dim, int* grid) {
+  static int cache[64][2];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return HFX_ERR_DEVICE;
+  const int slot = head_dim == 128 ? 1 : 0;
+  if (dev >= 0 && dev < 64 && cache[dev][slot] > 0) {
+    *grid = cache[dev][slot];
+    return HFX_OK;
+  }
+  int cus = 0, per_cu = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return HFX_ERR_DEVICE;
+  if (hfx::max_resident_workgroups(head_dim, &per_cu) != hipSuccess) return HFX_ERR_DEVICE;
+  if (cus < 1 || per_cu < 1) return HFX_ERR_DEVICE;
+  *grid = cus * per_cu;
+  if (dev >= 0 && dev < 64) cache[dev][slot] = *grid;
+  return HFX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hfx_status_string(hfx_status s) {
+  switch (s) {
+    case HFX_OK: return "ok";
+    case HFX_ERR_NULL: return "null pointer";
+    case HFX_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case HFX_ERR_KIND: return "request kind is neither decode nor prefill";
+    case HFX_ERR_LEN: return "query-chunk / context length out of range";
+    case HFX_ERR_PAGES: return "block table malformed or too short";
+    case HFX_ERR_PAGE_ID: return "page id outside the pool";
+    case HFX_ERR_BUFSIZE: return "buffer too small";
+    case HFX_ERR_DEVICE: return "HIP runtime error";
+    case HFX_ERR_DESC: return "not a batch descriptor of this library version";
+    case HFX_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+hfx_status hfx_version(int32_t* major, int32_t* minor) {
+  if (major) *major = 0;
+  if (minor) *minor = (int32_t)HFX_DESC_VERSION;
+  return HFX_OK;
+}
+
+hfx_status hfx_batch_desc_sizes(const hfx_shape* shape, int32_t num_requests, const int32_t* kind,
+                                const int32_t* q_len, const int32_t* ctx_len, size_t* host_desc_bytes,
+                                size_t* device_desc_bytes, size_t* device_workspace_bytes) {
+  if (!host_desc_bytes || !device_desc_bytes || !device_workspace_bytes) return HFX_ERR_NULL;
+  hfx::Plan plan;
+  hfx_status st = hfx::plan_step(shape, num_requests, kind, q_len, ctx_len, &plan);
+  if (st != HFX_OK) return st;
+  HfxHeader h;
+  hfx::layout_blob(shape, plan, &h);
+  *host_desc_bytes = (size_t)h.total_bytes;
+  *device_desc_bytes = (size_t)h.total_bytes;
+  *device_workspace_bytes = (size_t)h.workspace_bytes;
+  return HFX_OK;
+}
+
+hfx_status hfx_fill_batch_desc(const hfx_shape* shape, int32_t num_requests, const int32_t* kind,
+                               const int32_t* q_len, const int32_t* ctx_len, const int32_t* bt_indptr,
+                               const int32_t* bt_pages, void* host_desc, size_t host_desc_bytes) {
+  hfx::Plan plan;
+  hfx_status st = hfx::plan_step(shape, num_requests, kind, q_len, ctx_len, &plan);
+  if (st != HFX_OK) return st;
+  return hfx::fill_blob(shape, plan, bt_indptr, bt_pages, host_desc, host_desc_bytes);
+}
+
+hfx_status hfx_build_batch_desc(const hfx_shape* shape, int32_t num_requests, const int32_t* kind,
+                                const int32_t* q_len, const int32_t* ctx_len, const int32_t* bt_indptr,
+                                const int32_t* bt_pages, void* host_desc, size_t host_desc_bytes,
+                                void* device_desc, size_t device_desc_bytes, void* stream) {
+  if (!device_desc) return HFX_ERR_NULL;
+  if (!aligned16(device_desc)) return HFX_ERR_ALIGN;
+  hfx_status st = hfx_fill_batch_desc(shape, num_requests, kind, q_len, ctx_len, bt_indptr, bt_pages, host_desc,
+                                      host_desc_bytes);
+  if (st != HFX_OK) return st;
+  HfxHeader h;
+  std::memcpy(&h, host_desc, sizeof h);
+  if (device_desc_bytes < h.total_bytes) return HFX_ERR_BUFSIZE;
+  if (hipMemcpyAsync(device_desc, host_desc, (size_t)h.total_bytes, hipMemcpyHostToDevice,
+                     static_cast<hipStream_t>(stream)) != hipSuccess)
+    return HFX_ERR_DEVICE;
+  return HFX_OK;
+}
+
+hfx_status hfx_mixed_paged_attention(const hfx_shape* shape, const void* q, const void* kv_pool,
+                                     const void* host_desc, void* device_desc, void* workspace,
+                                     size_t workspace_bytes, void* out, void* stream) {
+  if (!q || !kv_pool || !device_desc || !out) return HFX_ERR_NULL;
+  HfxHeader h;
+  hfx_status st = check_header(shape, host_desc, &h);
+  if (st != HFX_OK) return st;
+  if (h.workspace_bytes > 0 && !workspace) return HFX_ERR_NULL;
+  if (workspace_bytes < h.workspace_bytes) return HFX_ERR_BUFSIZE;
+  if (!aligned16(q) || !aligned16(kv_pool) || !aligned16(device_desc) || !aligned16(out) ||
+      (h.workspace_bytes > 0 && !aligned16(workspace)))
+    return HFX_ERR_ALIGN;
+  if (h.n_items < 1) return HFX_ERR_DESC;
+  int grid = 0;
+  st = persistent_grid(h.head_dim, &grid);
+  if (st != HFX_OK) return st;
+  if (grid > h.n_items) grid = h.n_items;
+  if (hfx::launch_mixed_attention(h.head_dim, grid, device_desc, q, kv_pool, workspace, out,
+                                  static_cast<hipStream_t>(stream)) != hipSuccess)
+    return HFX_ERR_DEVICE;
+  return HFX_OK;
+}
+
+hfx_status hfx_gather_kv(const hfx_shape* shape, const void* kv_pool, const void* host_desc,
+                         const void* device_desc, int32_t request, void* k_out, void* v_out, void* stream) {
+  if (!kv_pool || !device_desc || !k_out || !v_out) return HFX_ERR_NULL;
+  HfxHeader h;
+  hfx_status st = check_header(shape, host_desc, &h);
+  if (st != HFX_OK) return st;
+  if (request < 0 || request >= h.num_requests) return HFX_ERR_LEN;
+  const HfxReq* reqs = reinterpret_cast<const HfxReq*>(static_cast<const char*>(host_desc) + h.off_req);
+  const long elements = (long)reqs[request].ctx_len * h.num_kv_heads * h.head_dim;
+  if (hfx::launch_gather_kv(device_desc, kv_pool, request, elements, k_out, v_out,
+                            static_cast<hipStream_t>(stream)) != hipSuccess)
+    return HFX_ERR_DEVICE;
+  return HFX_OK;
+}
+
+}  // extern "C"

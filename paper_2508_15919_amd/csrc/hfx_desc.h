@@ -1,0 +1,58 @@
+// Internal layout of the batch descriptor shared by the host planner and the kernels.
+// Plain-old-data, position independent: the blob is built on the host and copied verbatim.
+#pragma once
+#include <stdint.h>
+
+#define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
+#define HFX_DESC_VERSION 3u
+#define HFX_PAGE 16
+#define HFX_WG_THREADS 256
+#define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
+#define HFX_KEY_TILE 64          /* keys per prefill tile (4 pages) */
+#define HFX_ROW_BLOCK 32         /* query rows one wavefront owns in a prefill item */
+
+enum { HFX_ITEM_DECODE = 0, HFX_ITEM_PREFILL = 1 };
+
+struct HfxHeader {
+  uint32_t magic, version;
+  int32_t num_requests, total_q;
+  int32_t num_q_heads, num_kv_heads, head_dim, page_size, num_pages;
+  float softmax_scale;
+  int32_t n_items, n_decode_items, n_prefill_items, n_groups;
+  int32_t n_partial_rows;       /* workspace rows: one (query row, q-head) partial each */
+  int32_t n_bt;                 /* page ids stored */
+  uint32_t off_ctrl, off_req, off_bt, off_items, off_groups;
+  uint32_t n_ctrl;              /* control words: [0] queue head, [1] finished workgroups, [2+i] group i arrivals */
+  uint64_t total_bytes;
+  uint64_t workspace_bytes;
+  uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */
+  uint32_t reserved[8];
+};
+
+struct HfxReq {
+  int32_t kind, q_len, ctx_len;
+  int32_t q_start;              /* first packed query row */
+  int32_t bt_start;             /* first entry in the stored block table */
+  int32_t n_pages;              /* ceil(ctx_len / 16) entries stored */
+  int32_t pad0, pad1;
+};
+
+// One unit of work for one workgroup.
+//  decode : h0 = first kv-head, hn = kv-heads covered (1, 2 or 4; one wavefront per head, the
+//           remaining wavefronts split the pages), kb/ke = request-relative page range.
+//  prefill: h0 = first q-head, hn = q-heads covered (1, 2 or 4), row0 = first chunk row,
+//           nrows = rows covered (32 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
+//  group >= 0: the item is one of several splits; its partial goes to workspace rows
+//           [slot_row, slot_row + rows) and the last arrival of the group merges.
+struct HfxItem {
+  int32_t type, req, group, slot_row;
+  int32_t h0, hn, row0, nrows;
+  int32_t kb, ke, cost, pad;
+};
+
+struct HfxGroup {
+  int32_t nsplit;
+  int32_t base_row;             /* workspace row of split 0 */
+  int32_t rows_per_split;
+  int32_t pad;
+};

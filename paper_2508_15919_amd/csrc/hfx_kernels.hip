@@ -1,0 +1,599 @@
+// Device code of libhfxattn for gfx950 (MI355X): one persistent kernel that drains the
+// cost-ordered work items of a scheduled step -- decode ranges (HBM-bound streaming of KV
+// pages, HFX Section 2.1 "generation phase") and prefill tiles (dense bf16 MFMA contraction
+// with a causal mask, Section 2.1 "prompt phase") -- plus the split merge and the page
+// gather hook.  Wavefronts are 64 lanes wide; every tiling below is written for that.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hfx_desc.h"
+#include "hfx_launch.h"
+
+namespace hfx {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define NEG_INF (-__builtin_inff())
+
+struct KArgs {
+  char* desc;            // device descriptor blob
+  const __bf16* q;       // [T][Hq][D]
+  const __bf16* pool;    // [pages][Hkv][2][16*D]
+  float* ws;             // split partials
+  __bf16* out;           // [T][Hq][D]
+};
+
+template <int D>
+struct Smem {
+  // prefill: K tile, token-major rows padded by 16 B; V tile, [page][token half][d][8 tokens]
+  static constexpr int kKStride = D * 2 + 16;
+  static constexpr int kKBytes = HFX_KEY_TILE * kKStride;
+  static constexpr int kVRegion = D * 16 + 128;
+  static constexpr int kVBytes = 8 * kVRegion;
+  // decode: per-wavefront partial rows [4][16][D + 4] floats
+  static constexpr int kPartStride = D + 4;
+  static constexpr int kPartBytes = 4 * 16 * kPartStride * 4;
+  static constexpr int kBytes = (kKBytes + kVBytes) > kPartBytes ? (kKBytes + kVBytes) : kPartBytes;
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// zero the elements e >= nv of an 8-element bf16 vector (nv may be <= 0 or >= 8)
+__device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
+  u32x4 u = __builtin_bit_cast(u32x4, v);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint32_t m = (2 * w < nv ? 0x0000ffffu : 0u) | (2 * w + 1 < nv ? 0xffff0000u : 0u);
+    u[w] &= m;
+  }
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// ----------------------------------------------------------------------------------------------
+// Split merge: the last split of a group to arrive combines the partial (m, l, acc) rows.
+//   m* = max m_s,  l* = sum l_s 2^(m_s - m*),  out = sum acc_s 2^(m_s - m*) / l*
+// (m is kept in the base-2 domain throughout.)
+// ----------------------------------------------------------------------------------------------
+template <int D>
+__device__ void merge_group(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq,
+                            const HfxGroup& gr) {
+  const int tid = threadIdx.x;
+  const int Hq = H->num_q_heads;
+  const int G = Hq / H->num_kv_heads;
+  const float* acc = a.ws;
+  const float* ml = reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.ws) + H->ws_off_ml);
+  const int rows = gr.rows_per_split, ns = gr.nsplit, base = gr.base_row;
+  constexpr int C4 = D / 4;
+  for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
+    const int row = idx / C4, d4 = (idx % C4) * 4;
+    long orow;
+    if (it.type == HFX_ITEM_DECODE) {
+      orow = (long)rq.q_start * Hq + it.h0 * G + row;
+    } else {
+      const int w = row >> 5, nn = row & 31;
+      const int head = it.h0 + w % it.hn;
+      const int qrow = it.row0 + (w / it.hn) * HFX_ROW_BLOCK + nn;
+      if (qrow >= rq.q_len) continue;
+      orow = ((long)rq.q_start + qrow) * Hq + head;
+    }
+    float mm = NEG_INF;
+    for (int s = 0; s < ns; ++s) mm = fmaxf(mm, ml[((long)base + (long)s * rows + row) * 2]);
+    float ll = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < ns; ++s) {
+      const long pr = (long)base + (long)s * rows + row;
+      const float w = fast_exp2(ml[pr * 2] - mm);
+      ll += ml[pr * 2 + 1] * w;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(acc + pr * D + d4);
+      o += v * w;
+    }
+    const float inv = 1.0f / ll;
+    bf16x4 ob;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[e] * inv);
+    *reinterpret_cast<bf16x4*>(a.out + orow * D + d4) = ob;
+  }
+}
+
+// Publishes this item's partial and reports whether this workgroup is the group's last arrival.
+__device__ __forceinline__ bool arrive_last(int* ctrl, int group, int nsplit, int* s_flag) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = atomicAdd(&ctrl[2 + group], 1);
+    const int last = (old == nsplit - 1);
+    if (last) atomicExch(&ctrl[2 + group], 0);
+    *s_flag = last;
+  }
+  __syncthreads();
+  const bool last = *s_flag != 0;
+  if (last) __threadfence();
+  return last;
+}
+
+// ----------------------------------------------------------------------------------------------
+// Decode item.  One wavefront per kv-head (hn of them), the other 4/hn wavefronts of the
+// workgroup interleave over page pairs.  Per pair (32 tokens) and kv-head a wavefront issues
+// 16 coalesced 16-byte loads per lane and 16 MFMA 16x16x32:
+//   S^T[token][head] = K[token][:] . Q[head][:]      (A = K rows, B = Q^T)
+//   O^T[d][head]    += V^T[d][token] . P^T[token][head]   (A = V^T rows, B = P^T)
+// The two 16-token score tiles take their rows from the page pair such that, in the MFMA
+// result layout, each lane ends up holding 8 consecutive tokens of one page -- exactly the
+// 16 bytes of a dimension-major V row that the second contraction needs, with no shuffles.
+// ----------------------------------------------------------------------------------------------
+template <int D>
+struct PairRegs {
+  bf16x8 ka[D / 32], kb[D / 32], v[D / 16];
+};
+
+template <int D>
+__device__ __forceinline__ void decode_load(PairRegs<D>& r, const __bf16* pool, const int* bt, int last_page,
+                                            int pp, int Hkv, int g, int k_sel, int k_off, int v_sel, int v_off) {
+  const int i0 = pp < last_page ? pp : last_page;
+  const int i1 = pp + 1 < last_page ? pp + 1 : last_page;
+  const int pg0 = bt[i0], pg1 = bt[i1];
+  constexpr long kBlock = 16 * D;
+  const __bf16* kp = pool + (((long)(k_sel ? pg1 : pg0) * Hkv + g) * 2) * kBlock + k_off;
+  const __bf16* vp = pool + (((long)(v_sel ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock + v_off;
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    r.ka[kk] = ld16(kp + kk * 32);
+    r.kb[kk] = ld16(kp + 4 * D + kk * 32);
+  }
+#pragma unroll
+  for (int b = 0; b < D / 16; ++b) r.v[b] = ld16(vp + b * 256);
+}
+
+template <int D>
+__device__ __forceinline__ void decode_compute(PairRegs<D>& r, const bf16x8* qf, f32x4* o, float& m, float& l,
+                                               float sl2, int nv) {
+  f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.ka[kk], qf[kk], sa, 0, 0, 0);
+    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.kb[kk], qf[kk], sb, 0, 0, 0);
+  }
+  float s[8];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    s[e] = sa[e] * sl2;
+    s[4 + e] = sb[e] * sl2;
+  }
+  if (nv < 8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = (e < nv) ? s[e] : NEG_INF;
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float mn = fmaxf(m, mx);
+  const float alpha = fast_exp2(m - mn);
+  float ps = 0.f;
+  bf16x8 pb;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float p = fast_exp2(s[e] - mn);
+    ps += p;
+    pb[e] = (__bf16)p;
+  }
+  l = l * alpha + ps;
+  m = mn;
+#pragma unroll
+  for (int b = 0; b < D / 16; ++b) {
+    o[b] *= alpha;
+    const bf16x8 vv = (nv < 8) ? keep_first(r.v[b], nv) : r.v[b];
+    o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, pb, o[b], 0, 0, 0);
+  }
+}
+
+template <int D>
+__device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem,
+                            int* ctrl, int* s_flag) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
+  const int G = Hq / Hkv;
+  const int HW = it.hn, TW = 4 / HW;
+  const int hw = wave % HW, tw = wave / HW;
+  const int g = it.h0 + hw;
+  const int n = lane & 15, j = lane >> 4;
+  const float sl2 = H->softmax_scale * 1.4426950408889634f;
+
+  bf16x8 qf[D / 32];
+  {
+    const int hh = n < G ? n : G - 1;
+    const __bf16* qrow = a.q + ((long)rq.q_start * Hq + g * G + hh) * D + j * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+      bf16x8 t = ld16(qrow + kk * 32);
+      qf[kk] = keep_first(t, n < G ? 8 : 0);
+    }
+  }
+  f32x4 o[D / 16];
+#pragma unroll
+  for (int b = 0; b < D / 16; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = NEG_INF, l = 0.f;
+
+  const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
+  const int last_page = rq.n_pages - 1;
+  const int pe = it.ke;
+  const int tend = min(pe * HFX_PAGE, rq.ctx_len);
+  // K rows of the two score tiles: row rho of tile A is (page rho>>3, token ((rho>>2)&1)*8 + (rho&3)),
+  // tile B the same + 4 tokens.  V: lane group j reads tokens (j&1)*8.. of page j>>1 for row d = 16b + n.
+  const int k_sel = n >> 3;
+  const int k_off = (((n >> 2) & 1) * 8 + (n & 3)) * D + j * 8;
+  const int v_sel = j >> 1;
+  const int v_off = n * 16 + (j & 1) * 8;
+  const int tok_lane = (j >> 1) * 16 + (j & 1) * 8;   // first of this lane's 8 tokens inside the pair
+  const int step = 2 * TW;
+
+  PairRegs<D> r0, r1;
+  int pp = it.kb + 2 * tw;
+  if (pp < pe) decode_load<D>(r0, a.pool, bt, last_page, pp, Hkv, g, k_sel, k_off, v_sel, v_off);
+  while (pp < pe) {
+    if (pp + step < pe) decode_load<D>(r1, a.pool, bt, last_page, pp + step, Hkv, g, k_sel, k_off, v_sel, v_off);
+    {
+      const int nv = tend - (pp * HFX_PAGE + tok_lane);
+      if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r0, qf, o, m, l, sl2, 8);
+      else decode_compute<D>(r0, qf, o, m, l, sl2, nv);
+    }
+    pp += step;
+    if (pp >= pe) break;
+    if (pp + step < pe) decode_load<D>(r0, a.pool, bt, last_page, pp + step, Hkv, g, k_sel, k_off, v_sel, v_off);
+    {
+      const int nv = tend - (pp * HFX_PAGE + tok_lane);
+      if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r1, qf, o, m, l, sl2, 8);
+      else decode_compute<D>(r1, qf, o, m, l, sl2, nv);
+    }
+    pp += step;
+  }
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+
+  // wavefront partial -> LDS: part[wave][head n][D + 4]; o[b][v] is dimension 16b + 4j + v
+  constexpr int PS = Smem<D>::kPartStride;
+  float* part = reinterpret_cast<float*>(smem);
+  if (n < G) {
+    float* dst = part + ((wave * 16 + n) * PS);
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b) *reinterpret_cast<f32x4*>(dst + b * 16 + 4 * j) = o[b];
+    if (j == 0) {
+      dst[D] = m;
+      dst[D + 1] = l;
+    }
+  }
+  __syncthreads();
+
+  // combine the TW token partitions of each head; row = hwi * G + hh
+  const int rows = HW * G;
+  float* ws_acc = a.ws;
+  float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
+  constexpr int C4 = D / 4;
+  for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
+    const int row = idx / C4, d4 = (idx % C4) * 4;
+    const int hwi = row / G, hh = row % G;
+    float mm = NEG_INF;
+    for (int t = 0; t < TW; ++t) mm = fmaxf(mm, part[((t * HW + hwi) * 16 + hh) * PS + D]);
+    float ll = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TW; ++t) {
+      const float* src = part + ((t * HW + hwi) * 16 + hh) * PS;
+      const float w = fast_exp2(src[D] - mm);
+      ll += src[D + 1] * w;
+      acc += *reinterpret_cast<const f32x4*>(src + d4) * w;
+    }
+    if (it.group < 0) {
+      const float inv = 1.0f / ll;
+      bf16x4 ob;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(acc[e] * inv);
+      *reinterpret_cast<bf16x4*>(a.out + ((long)rq.q_start * Hq + it.h0 * G + row) * D + d4) = ob;
+    } else {
+      const long pr = (long)it.slot_row + row;
+      *reinterpret_cast<f32x4*>(ws_acc + pr * D + d4) = acc;
+      if (d4 == 0) {
+        ws_ml[pr * 2] = mm;
+        ws_ml[pr * 2 + 1] = ll;
+      }
+    }
+  }
+  if (it.group >= 0) {
+    const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[it.group];
+    if (arrive_last(ctrl, it.group, gr.nsplit, s_flag)) merge_group<D>(a, H, it, rq, gr);
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Prefill item.  Four wavefronts, each owning a block of 32 chunk rows of one q-head; all four
+// share the kv-head, so one K/V tile (64 keys = 4 pages) staged in LDS serves them all.
+//   S^T[key][row]  = K[key][:] . Q[row][:]              (MFMA 32x32x16, A = K rows from LDS, B = Q^T in registers)
+//   O^T[d][row]   += V^T[d][key] . P^T[key][row]         (A = V^T rows from LDS, B = P^T from the score registers)
+// Each lane owns one query row (column of S^T and O^T), so the running max / sum / rescale are
+// lane-local up to one exchange with lane ^ 32.  The K rows of a score tile are taken in the
+// order that leaves every lane with 8 consecutive keys of one page per 16-key MFMA step.
+// ----------------------------------------------------------------------------------------------
+template <int D>
+struct StageRegs {
+  static constexpr int kChunks = 4 * 2 * D;   // 16-byte chunks of K (or of V) per 64-key tile
+  static constexpr int kPer = kChunks / HFX_WG_THREADS;
+  bf16x8 k[kPer], v[kPer];
+};
+
+template <int D>
+__device__ __forceinline__ void stage_load(StageRegs<D>& r, const __bf16* pool, const int* bt, int last_page,
+                                           int kt, int ctx, int Hkv, int g, int tid) {
+  constexpr int CH = 2 * D;   // 16-byte chunks per (page, head) K block
+  constexpr long kBlock = 16 * D;
+#pragma unroll
+  for (int i = 0; i < StageRegs<D>::kPer; ++i) {
+    const int c = i * HFX_WG_THREADS + tid;
+    const int pi = c / CH, w = c % CH;
+    const int lp = kt / HFX_PAGE + pi;
+    const int pg = bt[lp < last_page ? lp : last_page];
+    const __bf16* base = pool + (((long)pg * Hkv + g) * 2) * kBlock;
+    r.k[i] = ld16(base + w * 8);
+    bf16x8 vv = ld16(base + kBlock + w * 8);
+    if (kt + HFX_KEY_TILE > ctx) vv = keep_first(vv, ctx - (lp * HFX_PAGE + (w & 1) * 8));
+    r.v[i] = vv;
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void stage_store(const StageRegs<D>& r, char* smem, int tid) {
+  constexpr int CH = 2 * D;
+  constexpr int KS = Smem<D>::kKStride;
+  constexpr int VR = Smem<D>::kVRegion;
+  char* vbase = smem + Smem<D>::kKBytes;
+#pragma unroll
+  for (int i = 0; i < StageRegs<D>::kPer; ++i) {
+    const int c = i * HFX_WG_THREADS + tid;
+    const int pi = c / CH, w = c % CH;
+    // K chunk w: token w / (D/8), 16-byte column w % (D/8)
+    const int tok = w / (D / 8), col = w % (D / 8);
+    *reinterpret_cast<bf16x8*>(smem + (pi * 16 + tok) * KS + col * 16) = r.k[i];
+    // V chunk w: dimension w >> 1, token half w & 1
+    *reinterpret_cast<bf16x8*>(vbase + (pi * 2 + (w & 1)) * VR + (w >> 1) * 16) = r.v[i];
+  }
+}
+
+template <int D>
+__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem,
+                             int* ctrl, int* s_flag) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
+  const int G = Hq / Hkv;
+  const int head = it.h0 + wave % it.hn;
+  const int g = it.h0 / G;
+  const int r0 = it.row0 + (wave / it.hn) * HFX_ROW_BLOCK;
+  const int n = lane & 31, j = lane >> 5;
+  const int p = rq.ctx_len - rq.q_len;
+  const int qrow = r0 + n;
+  const int qrow_c = qrow < rq.q_len ? qrow : rq.q_len - 1;
+  const int pos = p + qrow_c;                                   // last key this row may see
+  const int wave_kend = r0 < rq.q_len ? p + min(r0 + HFX_ROW_BLOCK, rq.q_len) : 0;   // keys >= this: nothing to do
+  const int wave_pmin = p + r0;                                 // keys <= this are visible to every row
+  const float sl2 = H->softmax_scale * 1.4426950408889634f;
+
+  bf16x8 qf[D / 16];
+  {
+    const __bf16* qp = a.q + (((long)rq.q_start + qrow_c) * Hq + head) * D + j * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) qf[kk] = ld16(qp + kk * 16);
+  }
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[b][v] = 0.f;
+  float m = NEG_INF, l = 0.f;
+
+  const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
+  const int last_page = rq.n_pages - 1;
+  constexpr int KS = Smem<D>::kKStride;
+  constexpr int VR = Smem<D>::kVRegion;
+  // LDS row of this lane's K row in score sub-tile 0 (sub-tile u adds 32 rows)
+  const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
+  const char* k_lds = smem + krow * KS + j * 16;
+  const char* v_lds = smem + Smem<D>::kKBytes + j * VR + n * 16;
+
+  StageRegs<D> st;
+  stage_load<D>(st, a.pool, bt, last_page, it.kb, rq.ctx_len, Hkv, g, tid);
+  for (int kt = it.kb; kt < it.ke; kt += HFX_KEY_TILE) {
+    __syncthreads();
+    stage_store<D>(st, smem, tid);
+    __syncthreads();
+    if (kt + HFX_KEY_TILE < it.ke)
+      stage_load<D>(st, a.pool, bt, last_page, kt + HFX_KEY_TILE, rq.ctx_len, Hkv, g, tid);
+    if (kt >= wave_kend) continue;
+
+    f32x16 s[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[u][v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + u * 32 * KS + kk * 32);
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[u], 0, 0, 0);
+      }
+    }
+    // s[u][v] is key kt + (2u + (v>>3))*16 + j*8 + (v&7)
+    const bool need_mask = kt + HFX_KEY_TILE - 1 > wave_pmin;
+    float mx = NEG_INF;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float x = s[u][v] * sl2;
+        if (need_mask) {
+          const int key = kt + (2 * u + (v >> 3)) * 16 + j * 8 + (v & 7);
+          x = key <= pos ? x : NEG_INF;
+        }
+        s[u][v] = x;
+        mx = fmaxf(mx, x);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    const float ms = mn == NEG_INF ? 0.f : mn;
+    const float alpha = fast_exp2(m - ms);
+    float ps = 0.f;
+    bf16x8 pb[4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float pv = fast_exp2(s[u][v] - ms);
+        ps += pv;
+        pb[2 * u + (v >> 3)][v & 7] = (__bf16)pv;
+      }
+    l = l * alpha + ps;
+    m = mn;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) o[b] *= alpha;
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b) {
+        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_lds + sp * 2 * VR + b * 32 * 16);
+        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sp], o[b], 0, 0, 0);
+      }
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+
+  // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
+  if (it.group < 0) {
+    if (qrow < rq.q_len) {
+      const float inv = 1.0f / l;
+      __bf16* dst = a.out + (((long)rq.q_start + qrow) * Hq + head) * D + 4 * j;
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4 ob;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[b][q4 * 4 + e] * inv);
+          *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
+        }
+    }
+  } else {
+    float* ws_acc = a.ws;
+    float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
+    const long pr = (long)it.slot_row + wave * HFX_ROW_BLOCK + n;
+    float* dst = ws_acc + pr * D + 4 * j;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 t = {o[b][q4 * 4], o[b][q4 * 4 + 1], o[b][q4 * 4 + 2], o[b][q4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(dst + b * 32 + q4 * 8) = t;
+      }
+    if (j == 0) {
+      ws_ml[pr * 2] = m;
+      ws_ml[pr * 2 + 1] = l;
+    }
+    const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[it.group];
+    if (arrive_last(ctrl, it.group, gr.nsplit, s_flag)) merge_group<D>(a, H, it, rq, gr);
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// The persistent kernel: workgroups pull items in descending modelled cost until the queue is
+// empty.  The queue head and the arrival counters live in the descriptor; the last workgroup
+// to leave restores them to zero so the descriptor can serve the next launch.
+// ----------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(KArgs a) {
+  __shared__ __attribute__((aligned(16))) char smem[Smem<D>::kBytes];
+  __shared__ int s_item, s_flag;
+  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
+  int* ctrl = reinterpret_cast<int*>(a.desc + H->off_ctrl);
+  const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
+  const HfxReq* reqs = reinterpret_cast<const HfxReq*>(a.desc + H->off_req);
+  const int n_items = H->n_items;
+  for (;;) {
+    __syncthreads();
+    if (threadIdx.x == 0) s_item = atomicAdd(&ctrl[0], 1);
+    __syncthreads();
+    const int idx = uniform(s_item);
+    if (idx >= n_items) break;
+    const HfxItem it = items[idx];
+    const HfxReq rq = reqs[it.req];
+    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem, ctrl, &s_flag);
+    else prefill_item<D>(a, H, it, rq, smem, ctrl, &s_flag);
+  }
+  if (threadIdx.x == 0) {
+    const int done = atomicAdd(&ctrl[1], 1);
+    if (done == (int)gridDim.x - 1) {
+      atomicExch(&ctrl[0], 0);
+      atomicExch(&ctrl[1], 0);
+    }
+  }
+}
+
+// Page gather hook: one thread per (token, kv-head, dimension); a pure 2-byte copy through the
+// same request record and block table the attention kernel walks.
+__global__ void gather_kv_kernel(const char* desc, const uint16_t* pool, int request, uint16_t* k_out,
+                                 uint16_t* v_out) {
+  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(desc);
+  const HfxReq rq = reinterpret_cast<const HfxReq*>(desc + H->off_req)[request];
+  const int* bt = reinterpret_cast<const int*>(desc + H->off_bt) + rq.bt_start;
+  const int Hkv = H->num_kv_heads, D = H->head_dim;
+  const long total = (long)rq.ctx_len * Hkv * D;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int d = (int)(i % D);
+    const int g = (int)((i / D) % Hkv);
+    const long t = i / ((long)D * Hkv);
+    const long pg = bt[t / HFX_PAGE];
+    const int slot = (int)(t % HFX_PAGE);
+    const long blk = ((pg * Hkv + g) * 2) * (16L * D);
+    k_out[i] = pool[blk + (long)slot * D + d];
+    v_out[i] = pool[blk + 16L * D + (long)d * HFX_PAGE + slot];
+  }
+}
+
+// ------------------------------------------------------------------ host-side launch helpers
+hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
+  if (head_dim == 128)
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<128>, HFX_WG_THREADS, 0);
+  return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
+}
+
+hipError_t launch_mixed_attention(int head_dim, int grid, void* desc, const void* q, const void* pool, void* ws,
+                                  void* out, hipStream_t stream) {
+  KArgs a;
+  a.desc = static_cast<char*>(desc);
+  a.q = static_cast<const __bf16*>(q);
+  a.pool = static_cast<const __bf16*>(pool);
+  a.ws = static_cast<float*>(ws);
+  a.out = static_cast<__bf16*>(out);
+  if (head_dim == 128)
+    hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
+  else
+    hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
+                            void* v_out, hipStream_t stream) {
+  long blocks = (elements + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(gather_kv_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     static_cast<const char*>(desc), static_cast<const uint16_t*>(pool), request,
+                     static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out));
+  return hipGetLastError();
+}
+
+}  // namespace hfx

@@ -1,0 +1,13 @@
+// Host-callable launch helpers implemented next to the kernels (internal).
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+namespace hfx {
+
+hipError_t max_resident_workgroups(int head_dim, int* per_cu);
+hipError_t launch_mixed_attention(int head_dim, int grid, void* desc, const void* q, const void* pool, void* ws,
+                                  void* out, hipStream_t stream);
+hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
+                            void* v_out, hipStream_t stream);
+
+}  // namespace hfx

@@ -1,0 +1,257 @@
+// Host planner: turns the scheduler's statement of a step (HFX Section 3.3.1: which requests
+// run and how many new tokens each contributes) into the batch descriptor one persistent launch
+// drains.  Integer work only; no device calls in this file.
+#include "hfx_plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+namespace hfx {
+
+// Relative cost model, in nanoseconds of one resident workgroup when the whole chip runs that
+// kind of work: decode streams KV bytes (about 6 TB/s over HFX_PLAN_WGS workgroups), prefill
+// does MFMA flops (about 1 PFLOP/s over HFX_PLAN_WGS workgroups).  Only ratios matter: they
+// order the queue and size the splits.
+static const double kDecodeBytesPerNs = 12.0;
+static const double kPrefillFlopsPerNs = 2000.0;
+static const double kMinItemNs = 16000.0;
+static const int kMinDecodeTokens = 128;
+static const int kMinPrefillKeys = 256;
+static const int kMaxSplits = 64;
+static const int kItemsPerWg = 8;
+
+static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
+static int q_heads_per_item(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1); }
+
+hfx_status check_shape(const hfx_shape* s) {
+  if (!s) return HFX_ERR_NULL;
+  if (s->num_q_heads <= 0 || s->num_kv_heads <= 0) return HFX_ERR_SHAPE;
+  if (s->num_q_heads % s->num_kv_heads != 0) return HFX_ERR_SHAPE;
+  if (s->num_q_heads / s->num_kv_heads > 16) return HFX_ERR_SHAPE;
+  if (s->num_kv_heads > 2 && s->num_kv_heads % 4 != 0) return HFX_ERR_SHAPE;
+  if (s->head_dim != 64 && s->head_dim != 128) return HFX_ERR_SHAPE;
+  if (s->page_size != HFX_PAGE) return HFX_ERR_SHAPE;
+  if (s->num_pages < 1) return HFX_ERR_SHAPE;
+  if (!(s->softmax_scale == s->softmax_scale)) return HFX_ERR_SHAPE;
+  return HFX_OK;
+}
+
+// visible (row, key) pairs of chunk rows [r0, r1) against keys [kb, ke); row i sees keys <= p+i
+static int64_t pairs_in(int64_t p, int64_t r0, int64_t r1, int64_t kb, int64_t ke) {
+  int64_t n = 0;
+  for (int64_t i = r0; i < r1; ++i) {
+    int64_t hi = std::min<int64_t>(ke, p + i + 1);
+    if (hi > kb) n += hi - kb;
+  }
+  return n;
+}
+
+static int32_t clamp_cost(double ns) {
+  if (ns < 1.0) return 1;
+  if (ns > 2.0e9) return 2000000000;
+  return (int32_t)ns;
+}
+
+hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, const int32_t* q_len,
+                     const int32_t* ctx_len, Plan* out) {
+  hfx_status st = check_shape(shape);
+  if (st != HFX_OK) return st;
+  if (!kind || !q_len || !ctx_len || !out) return HFX_ERR_NULL;
+  if (R < 1) return HFX_ERR_SHAPE;
+  const int Hq = shape->num_q_heads, Hkv = shape->num_kv_heads, D = shape->head_dim;
+  const int G = Hq / Hkv;
+
+  Plan& P = *out;
+  P.reqs.assign((size_t)R, HfxReq());
+  P.items.clear();
+  P.groups.clear();
+  int64_t T = 0, nbt = 0;
+  double total_ns = 0.0;
+  for (int r = 0; r < R; ++r) {
+    if (kind[r] != HFX_DECODE && kind[r] != HFX_PREFILL) return HFX_ERR_KIND;
+    if (q_len[r] < 1 || ctx_len[r] < q_len[r]) return HFX_ERR_LEN;
+    if (kind[r] == HFX_DECODE && q_len[r] != 1) return HFX_ERR_LEN;
+    HfxReq& q = P.reqs[(size_t)r];
+    q.kind = kind[r];
+    q.q_len = q_len[r];
+    q.ctx_len = ctx_len[r];
+    q.n_pages = (int32_t)(((int64_t)ctx_len[r] + HFX_PAGE - 1) / HFX_PAGE);
+    if (T > 0x7fffffff - q_len[r] || nbt > 0x7fffffff - q.n_pages) return HFX_ERR_LEN;
+    q.q_start = (int32_t)T;
+    q.bt_start = (int32_t)nbt;
+    T += q_len[r];
+    nbt += q.n_pages;
+    if (kind[r] == HFX_DECODE) {
+      total_ns += (double)ctx_len[r] * Hkv * D * 4.0 / kDecodeBytesPerNs;
+    } else {
+      double ql = q_len[r], p = ctx_len[r] - q_len[r];
+      total_ns += 4.0 * D * Hq * (ql * p + ql * (ql + 1) / 2) / kPrefillFlopsPerNs;
+    }
+  }
+  P.total_q = (int32_t)T;
+  P.n_bt = (int32_t)nbt;
+  const double cap_ns = std::max(total_ns / (HFX_PLAN_WGS * kItemsPerWg), kMinItemNs);
+
+  int64_t rows = 0;
+  const int ngc = kv_heads_per_item(Hkv);
+  const int hpw = q_heads_per_item(G);
+  const int rows_wg = HFX_ROW_BLOCK * (4 / hpw);
+  for (int r = 0; r < R; ++r) {
+    const HfxReq& q = P.reqs[(size_t)r];
+    if (q.kind == HFX_DECODE) {
+      const double ns_per_token = (double)ngc * D * 4.0 / kDecodeBytesPerNs;
+      int64_t L = (int64_t)(cap_ns / ns_per_token);
+      L = std::max<int64_t>(L, kMinDecodeTokens);
+      L = std::max<int64_t>(L, ((int64_t)q.ctx_len + kMaxSplits - 1) / kMaxSplits);
+      int64_t pages_per = (L + HFX_PAGE - 1) / HFX_PAGE;
+      pages_per += pages_per & 1;                     // page pairs stay aligned across splits
+      int nsplit = (int)((q.n_pages + pages_per - 1) / pages_per);
+      // even out the pieces
+      pages_per = (q.n_pages + nsplit - 1) / nsplit;
+      pages_per += pages_per & 1;
+      nsplit = (int)((q.n_pages + pages_per - 1) / pages_per);
+      for (int g0 = 0; g0 < Hkv; g0 += ngc) {
+        int group = -1;
+        if (nsplit > 1) {
+          group = (int)P.groups.size();
+          HfxGroup gr = {nsplit, (int32_t)rows, ngc * G, 0};
+          P.groups.push_back(gr);
+        }
+        for (int s = 0; s < nsplit; ++s) {
+          HfxItem it;
+          std::memset(&it, 0, sizeof it);
+          it.type = HFX_ITEM_DECODE;
+          it.req = r;
+          it.group = group;
+          it.slot_row = (nsplit > 1) ? (int32_t)(rows + (int64_t)s * ngc * G) : -1;
+          it.h0 = g0;
+          it.hn = ngc;
+          it.kb = (int32_t)(s * pages_per);
+          it.ke = (int32_t)std::min<int64_t>(q.n_pages, (int64_t)(s + 1) * pages_per);
+          int64_t toks = std::min<int64_t>(q.ctx_len, (int64_t)it.ke * HFX_PAGE) - (int64_t)it.kb * HFX_PAGE;
+          it.cost = clamp_cost((double)toks * ns_per_token + 2000.0);
+          P.items.push_back(it);
+        }
+        if (nsplit > 1) rows += (int64_t)nsplit * ngc * G;
+      }
+    } else {
+      const int64_t p = q.ctx_len - q.q_len;
+      const int n_rt = (q.q_len + rows_wg - 1) / rows_wg;
+      for (int rt = 0; rt < n_rt; ++rt) {
+        const int64_t r0 = (int64_t)rt * rows_wg, r1 = std::min<int64_t>(q.q_len, r0 + rows_wg);
+        const int64_t kmax = p + r1;
+        const int64_t ntiles = (kmax + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
+        const double ns_all = 4.0 * D * hpw * (double)pairs_in(p, r0, r1, 0, kmax) / kPrefillFlopsPerNs;
+        int64_t nsplit = (int64_t)std::ceil(ns_all / cap_ns);
+        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kMaxSplits));
+        int64_t tiles_per = (ntiles + nsplit - 1) / nsplit;
+        tiles_per = std::max<int64_t>(tiles_per, kMinPrefillKeys / HFX_KEY_TILE);
+        nsplit = (ntiles + tiles_per - 1) / tiles_per;
+        for (int g = 0; g < Hkv; ++g)
+          for (int hb = 0; hb < G / hpw; ++hb) {
+            int group = -1;
+            if (nsplit > 1) {
+              group = (int)P.groups.size();
+              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_ROW_BLOCK, 0};
+              P.groups.push_back(gr);
+            }
+            for (int64_t s = 0; s < nsplit; ++s) {
+              HfxItem it;
+              std::memset(&it, 0, sizeof it);
+              it.type = HFX_ITEM_PREFILL;
+              it.req = r;
+              it.group = group;
+              it.slot_row = (nsplit > 1) ? (int32_t)(rows + s * 4 * HFX_ROW_BLOCK) : -1;
+              it.h0 = g * G + hb * hpw;
+              it.hn = hpw;
+              it.row0 = (int32_t)r0;
+              it.nrows = rows_wg;
+              it.kb = (int32_t)(s * tiles_per * HFX_KEY_TILE);
+              it.ke = (int32_t)std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
+              it.cost = clamp_cost(4.0 * D * hpw * (double)pairs_in(p, r0, r1, it.kb, it.ke) / kPrefillFlopsPerNs + 3000.0);
+              P.items.push_back(it);
+            }
+            if (nsplit > 1) rows += nsplit * 4 * HFX_ROW_BLOCK;
+          }
+      }
+    }
+    if (rows > 0x7fffffff / 2 || P.items.size() > 0x3fffffffu) return HFX_ERR_LEN;
+  }
+  P.n_partial_rows = (int32_t)rows;
+  std::stable_sort(P.items.begin(), P.items.end(),
+                   [](const HfxItem& a, const HfxItem& b) { return a.cost > b.cost; });
+  P.n_decode_items = P.n_prefill_items = 0;
+  for (const HfxItem& it : P.items) (it.type == HFX_ITEM_DECODE ? P.n_decode_items : P.n_prefill_items)++;
+  return HFX_OK;
+}
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
+  std::memset(h, 0, sizeof *h);
+  h->magic = HFX_DESC_MAGIC;
+  h->version = HFX_DESC_VERSION;
+  h->num_requests = (int32_t)P.reqs.size();
+  h->total_q = P.total_q;
+  h->num_q_heads = shape->num_q_heads;
+  h->num_kv_heads = shape->num_kv_heads;
+  h->head_dim = shape->head_dim;
+  h->page_size = shape->page_size;
+  h->num_pages = shape->num_pages;
+  h->softmax_scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / std::sqrt((float)shape->head_dim);
+  h->n_items = (int32_t)P.items.size();
+  h->n_decode_items = P.n_decode_items;
+  h->n_prefill_items = P.n_prefill_items;
+  h->n_groups = (int32_t)P.groups.size();
+  h->n_partial_rows = P.n_partial_rows;
+  h->n_bt = P.n_bt;
+  h->n_ctrl = (uint32_t)align_up(2 + P.groups.size(), 16);
+  uint64_t off = align_up(sizeof(HfxHeader), 256);
+  h->off_ctrl = (uint32_t)off;
+  off = align_up(off + 4ull * h->n_ctrl, 64);
+  h->off_req = (uint32_t)off;
+  off = align_up(off + sizeof(HfxReq) * P.reqs.size(), 64);
+  h->off_bt = (uint32_t)off;
+  off = align_up(off + 4ull * (uint64_t)P.n_bt, 64);
+  h->off_items = (uint32_t)off;
+  off = align_up(off + sizeof(HfxItem) * P.items.size(), 64);
+  h->off_groups = (uint32_t)off;
+  off = align_up(off + sizeof(HfxGroup) * P.groups.size(), 256);
+  h->total_bytes = off;
+  uint64_t acc_bytes = align_up((uint64_t)P.n_partial_rows * shape->head_dim * 4ull, 256);
+  h->ws_off_ml = acc_bytes;
+  h->workspace_bytes = P.n_partial_rows ? acc_bytes + align_up((uint64_t)P.n_partial_rows * 8ull, 256) : 0;
+}
+
+hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, const int32_t* bt_pages,
+                     void* host_desc, size_t host_desc_bytes) {
+  if (!bt_indptr || !bt_pages || !host_desc) return HFX_ERR_NULL;
+  HfxHeader h;
+  layout_blob(shape, P, &h);
+  if (h.total_bytes > 0xffffffffull) return HFX_ERR_LEN;
+  if (host_desc_bytes < h.total_bytes) return HFX_ERR_BUFSIZE;
+  const int R = (int)P.reqs.size();
+  if (bt_indptr[0] != 0) return HFX_ERR_PAGES;
+  for (int r = 0; r < R; ++r) {
+    if (bt_indptr[r + 1] < bt_indptr[r]) return HFX_ERR_PAGES;
+    if ((int64_t)bt_indptr[r + 1] - bt_indptr[r] < P.reqs[(size_t)r].n_pages) return HFX_ERR_PAGES;
+  }
+  for (int r = 0; r < R; ++r) {
+    const int32_t* src = bt_pages + bt_indptr[r];
+    for (int i = 0; i < P.reqs[(size_t)r].n_pages; ++i)
+      if (src[i] < 0 || src[i] >= shape->num_pages) return HFX_ERR_PAGE_ID;
+  }
+  char* base = (char*)host_desc;
+  std::memset(base, 0, (size_t)h.total_bytes);
+  std::memcpy(base, &h, sizeof h);
+  std::memcpy(base + h.off_req, P.reqs.data(), sizeof(HfxReq) * P.reqs.size());
+  int32_t* bt = (int32_t*)(base + h.off_bt);
+  for (int r = 0; r < R; ++r)
+    std::memcpy(bt + P.reqs[(size_t)r].bt_start, bt_pages + bt_indptr[r], 4ull * (size_t)P.reqs[(size_t)r].n_pages);
+  std::memcpy(base + h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size());
+  if (!P.groups.empty()) std::memcpy(base + h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size());
+  return HFX_OK;
+}
+
+}  // namespace hfx

@@ -1,0 +1,26 @@
+// Host planner interface (internal).  See hfx_plan.cpp.
+#pragma once
+#include <stddef.h>
+
+#include <vector>
+
+#include "../../include/hfxattn.h"
+#include "hfx_desc.h"
+
+namespace hfx {
+
+struct Plan {
+  std::vector<HfxReq> reqs;
+  std::vector<HfxItem> items;
+  std::vector<HfxGroup> groups;
+  int32_t total_q = 0, n_bt = 0, n_partial_rows = 0, n_decode_items = 0, n_prefill_items = 0;
+};
+
+hfx_status check_shape(const hfx_shape* shape);
+hfx_status plan_step(const hfx_shape* shape, int32_t num_requests, const int32_t* kind, const int32_t* q_len,
+                     const int32_t* ctx_len, Plan* out);
+void layout_blob(const hfx_shape* shape, const Plan& plan, HfxHeader* header);
+hfx_status fill_blob(const hfx_shape* shape, Plan& plan, const int32_t* bt_indptr, const int32_t* bt_pages,
+                     void* host_desc, size_t host_desc_bytes);
+
+}  // namespace hfx

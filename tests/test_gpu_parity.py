@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 CPU oracle, element by element.
+
+Tolerance (bf16 outputs, fp32 accumulation): max-abs <= 2e-2 and mean-abs <= 2e-3 over all
+outputs of a step.  Paging (gather) and results that are bf16-representable by construction
+are compared bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2508_15919_amd import synth
+from paper_2508_15919_amd.synth import DECODE, PREFILL, bf16_bits_to_f64
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+@pytest.fixture(scope="module")
+def hb():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2508_15919_amd import binding
+    binding.load()
+    return binding
+
+
+def report(b, err):
+    qi = b.q_indptr()
+    lines = []
+    for r in range(b.num_requests):
+        e = err[qi[r]:qi[r + 1]]
+        lines.append(f"  req {r} kind {int(b.kind[r])} q {int(b.q_len[r])} c {int(b.ctx_len[r])}: "
+                     f"max {np.nanmax(e):.3e} nan {int(np.isnan(e).sum())} per-head {np.round(np.nanmax(e, axis=(0, 2)), 4).tolist()}")
+    return "\n".join(lines[:40])
+
+
+def run_gpu(hb, b):
+    step = hb.DeviceStep(b)
+    step.run()
+    return step, step.out_bits()
+
+
+def check_full(hb, oracle, b):
+    step, bits = run_gpu(hb, b)
+    got = bf16_bits_to_f64(bits)
+    ref = oracle.attention_batch(b)
+    err = np.abs(got - ref)
+    msg = f"{b.name}: max {np.nanmax(err):.3e} mean {np.nanmean(err):.3e}\n" + report(b, err)
+    print(f"{b.name}: T={b.total_q} max-abs {np.nanmax(err):.3e} mean-abs {np.nanmean(err):.3e}", flush=True)
+    assert np.isfinite(got).all(), msg
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, msg
+    return step, bits
+
+
+def check_sampled(hb, oracle, b, n_rows, seed):
+    """Full-size steps: all decode requests on sampled heads, prefill rows sampled with every chunk's first
+    and last row and rows around page / tile edges always included."""
+    step, bits = run_gpu(hb, b)
+    got = bf16_bits_to_f64(bits)
+    assert np.isfinite(got).all(), f"{b.name}: non-finite outputs"
+    g = np.random.default_rng(seed)
+    qi = b.q_indptr()
+    req, row, head = [], [], []
+    for r in range(b.num_requests):
+        ql = int(b.q_len[r])
+        if b.kind[r] == DECODE:
+            for h in g.choice(b.num_q_heads, min(4, b.num_q_heads), replace=False):
+                req.append(r); row.append(0); head.append(int(h))
+        else:
+            fixed = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, ql - 2, ql - 1]
+            rows = sorted(set(i for i in fixed if 0 <= i < ql) | set(g.integers(0, ql, n_rows).tolist()))
+            for i in rows:
+                req.append(r); row.append(i); head.append(int(g.integers(0, b.num_q_heads)))
+    ref = oracle.attention_rows_batch(b, req, row, head)
+    sel = got[qi[np.array(req)] + np.array(row), np.array(head)]
+    err = np.abs(sel - ref)
+    print(f"{b.name}: {len(req)} sampled rows, max-abs {err.max():.3e} mean-abs {err.mean():.3e}", flush=True)
+    worst = np.argsort(err.max(axis=1))[-5:]
+    msg = f"{b.name}: worst " + str([(req[i], row[i], head[i], float(err[i].max())) for i in worst])
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, msg
+    return step
+
+
+def test_config1_tiny_mixed(hb, oracle):
+    check_full(hb, oracle, synth.config(1))
+
+
+@pytest.mark.parametrize("idx,scale", [(2, 0.25), (3, 0.1), (4, 0.12), (5, 0.05)])
+def test_scaled_configs_full_compare(hb, oracle, idx, scale):
+    check_full(hb, oracle, synth.config(idx, scale))
+
+
+def test_config2_full_size(hb, oracle):
+    check_full(hb, oracle, synth.config(2))
+
+
+@pytest.mark.timeout(600)
+def test_config3_full_size_sampled(hb, oracle):
+    check_sampled(hb, oracle, synth.config(3), 0, 3)
+
+
+@pytest.mark.timeout(600)
+def test_config4_full_size_sampled(hb, oracle):
+    check_sampled(hb, oracle, synth.config(4), 160, 4)
+
+
+@pytest.mark.timeout(600)
+def test_config5_full_size_sampled(hb, oracle):
+    check_sampled(hb, oracle, synth.config(5), 256, 5)
+
+
+def test_single_token_context_returns_v_bit_exact(hb):
+    b = synth.make_batch(32, 8, 128, [DECODE, PREFILL, DECODE], [1, 1, 1], [1, 1, 1], 5)
+    _, bits = run_gpu(hb, b)
+    for r in range(3):
+        page = b.bt_pages[b.bt_indptr[r]]
+        v = b.pool[page, :, 1].reshape(8, 128, 16)[:, :, 0]           # [g, d] at slot 0
+        for h in range(32):
+            assert np.array_equal(bits[r, h], v[h // 4]), (r, h)
+
+
+def test_page_permutation_gives_identical_bits(hb):
+    for b in (synth.config(1), synth.config(2, 0.25), synth.config(5, 0.05)):
+        _, a = run_gpu(hb, b)
+        _, c = run_gpu(hb, synth.permute_pages(b, 9))
+        assert np.array_equal(a, c), b.name
+
+
+def test_gather_is_bit_exact(hb, oracle):
+    for b in (synth.config(1), synth.config(2, 0.1)):
+        step = hb.DeviceStep(b)
+        for r in range(b.num_requests):
+            k, v = step.gather(r)
+            ok, ov = oracle.gather_kv(b.num_kv_heads, b.head_dim, b.num_pages, b.ctx_len, b.bt_indptr, b.bt_pages,
+                                      b.pool, r)
+            assert np.array_equal(k, ok) and np.array_equal(v, ov), (b.name, r)
+
+
+def test_descriptor_serves_repeated_launches(hb):
+    import torch
+    b = synth.config(4, 0.12)
+    step = hb.DeviceStep(b)
+    step.run()
+    first = step.out_bits().copy()
+    for _ in range(3):
+        step.out.zero_()
+        step.run()
+        assert np.array_equal(step.out_bits(), first)
+    torch.cuda.synchronize()
+    d = hb.parse_desc(step.device_desc.cpu().numpy())
+    assert np.all(d["ctrl"] == 0), "control words must be restored to zero"
+    assert d["header"].n_groups > 0
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 64), (2, 2, 128), (16, 1, 64), (16, 1, 128), (12, 4, 128), (8, 8, 128),
+                                      (6, 2, 64)])
+def test_head_layouts_and_ragged_lengths(hb, oracle, Hq, Hkv, D):
+    kinds = [PREFILL, DECODE, PREFILL, DECODE, PREFILL, DECODE, PREFILL, DECODE]
+    ql = [1, 1, 33, 1, 130, 1, 64, 1]
+    cl = [1, 16, 33, 500, 700, 17, 64, 2049]
+    check_full(hb, oracle, synth.make_batch(Hq, Hkv, D, kinds, ql, cl, 100 + Hq + D, extra_pages_per_request=1))
+
+
+def test_shared_prefix_pages(hb, oracle):
+    b = synth.make_batch(32, 8, 128, [DECODE, DECODE, PREFILL], [1, 1, 40], [300, 300, 296], 13)
+    n = 16
+    for r in (1, 2):
+        b.bt_pages[b.bt_indptr[r]:b.bt_indptr[r] + n] = b.bt_pages[0:n]      # first 256 tokens shared
+    check_full(hb, oracle, b)
+
+
+def test_table1_short_context_step(hb, oracle):
+    check_full(hb, oracle, synth.table1_short_context())
+
+
+def test_custom_softmax_scale(hb, oracle):
+    b = synth.config(1)
+    step = hb.DeviceStep(b, softmax_scale=0.05)
+    step.run()
+    got = bf16_bits_to_f64(step.out_bits())
+    ref = oracle.attention_batch(b, scale=float(np.float32(0.05)))
+    assert np.abs(got - ref).max() <= MAX_ABS
+
+
+def test_device_side_errors(hb):
+    import torch
+    b = synth.config(1)
+    step = hb.DeviceStep(b)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hb.HfxError) as e:
+        hb.hfx_build_batch_desc(step.shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, step.host_desc,
+                                small, torch.cuda.current_stream())
+    assert e.value.code == hb.HFX_ERR_BUFSIZE
+    with pytest.raises(hb.HfxError) as e:
+        hb.hfx_gather_kv(step.shape, step.pool, step.host_desc, step.device_desc, 99, step.q, step.q)
+    assert e.value.code == hb.HFX_ERR_LEN
+    big = synth.config(4, 0.12)
+    s2 = hb.DeviceStep(big)
+    assert s2.workspace_bytes > 0
+    with pytest.raises(hb.HfxError) as e:
+        hb.hfx_mixed_paged_attention(s2.shape, s2.q, s2.pool, s2.host_desc, s2.device_desc, small, s2.out)
+    assert e.value.code == hb.HFX_ERR_BUFSIZE

@@ -1,0 +1,201 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, validates
+its inputs, and the planner's work items cover every decode token and every visible prefill
+(row, key) pair exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2508_15919_amd import binding as hb
+from paper_2508_15919_amd import synth
+from paper_2508_15919_amd.synth import DECODE, PREFILL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hb.LIB_PATH):
+        from paper_2508_15919_amd import build
+        build.build()
+    return hb.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "hfxattn.h")).read()
+    declared = set(re.findall(r"\b(hfx_[a-z_]+)\s*\(", header))
+    assert declared == set(hb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert hb.hfx_status_string(0) == "ok" and "page id" in hb.hfx_status_string(hb.HFX_ERR_PAGE_ID)
+    assert hb.hfx_version()[1] >= 1
+
+
+def fill(b, scale=0.0):
+    shape = hb.make_shape(b.num_q_heads, b.num_kv_heads, b.head_dim, b.num_pages, scale)
+    hbts, dbts, wbts = hb.hfx_batch_desc_sizes(shape, b.kind, b.q_len, b.ctx_len)
+    host = np.zeros(hbts, np.uint8)
+    hb.hfx_fill_batch_desc(shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, host)
+    d = hb.parse_desc(host)
+    assert d["header"].total_bytes == hbts == dbts and d["header"].workspace_bytes == wbts
+    return d
+
+
+def lengths_only(Hq, Hkv, D, kind, q_len, ctx_len):
+    """A step with a block table but a one-page dummy pool (the planner never reads the pool)."""
+    kind, q_len, ctx_len = (np.asarray(a, np.int32) for a in (kind, q_len, ctx_len))
+    npg = (ctx_len.astype(np.int64) + 15) // 16
+    indptr = np.zeros(len(kind) + 1, np.int32)
+    indptr[1:] = np.cumsum(npg)
+    pages = np.arange(int(npg.sum()), dtype=np.int32)[::-1].copy()
+    return synth.StepBatch(Hq, Hkv, D, max(1, int(npg.sum())), kind, q_len, ctx_len, indptr, pages,
+                           np.zeros((int(q_len.sum()), Hq, D), np.uint16), np.zeros((1, Hkv, 2, 16 * D), np.uint16))
+
+
+def check_coverage(b, d):
+    h, items, reqs, groups = d["header"], d["items"], d["reqs"], d["groups"]
+    Hq, Hkv = b.num_q_heads, b.num_kv_heads
+    G = Hq // Hkv
+    assert h.n_items == len(items) == h.n_decode_items + h.n_prefill_items
+    assert np.all(np.diff(items["cost"]) <= 0), "queue must be in descending modelled cost"
+    assert np.all(d["ctrl"] == 0)
+    # stored block table: exactly the needed pages, in order
+    for r in range(b.num_requests):
+        n = int(reqs["n_pages"][r])
+        assert n == (int(b.ctx_len[r]) + 15) // 16
+        assert np.array_equal(d["bt"][reqs["bt_start"][r]:reqs["bt_start"][r] + n],
+                              b.bt_pages[b.bt_indptr[r]:b.bt_indptr[r] + n])
+    qi = b.q_indptr()
+    assert np.array_equal(reqs["q_start"], qi[:-1])
+    slot_owner = np.zeros(max(1, h.n_partial_rows), np.int32)
+    group_count = np.zeros(max(1, h.n_groups), np.int32)
+    for r in range(b.num_requests):
+        mine = items[items["req"] == r]
+        c, ql = int(b.ctx_len[r]), int(b.q_len[r])
+        if b.kind[r] == DECODE:
+            assert np.all(mine["type"] == 0)
+            cover = np.zeros((Hkv, (c + 15) // 16), np.int32)
+            for it in mine:
+                assert it["hn"] in (1, 2, 4) and 0 <= it["kb"] < it["ke"] <= (c + 15) // 16 and it["kb"] % 2 == 0
+                cover[it["h0"]:it["h0"] + it["hn"], it["kb"]:it["ke"]] += 1
+            assert np.all(cover == 1)
+        else:
+            assert np.all(mine["type"] == 1)
+            p = c - ql
+            cover = np.zeros((Hq, ql, c), np.int16)
+            for it in mine:
+                assert it["hn"] in (1, 2, 4) and it["nrows"] == 32 * 4 // it["hn"] and it["kb"] % 64 == 0
+                assert it["h0"] // G == (it["h0"] + it["hn"] - 1) // G, "an item stays inside one kv group"
+                r1 = min(ql, it["row0"] + it["nrows"])
+                cover[it["h0"]:it["h0"] + it["hn"], it["row0"]:r1, it["kb"]:it["ke"]] += 1
+            visible = (np.arange(c)[None, :] <= (p + np.arange(ql))[:, None])
+            assert np.all(cover[:, visible] == 1), "every visible pair exactly once"
+        for it in mine:
+            if it["group"] >= 0:
+                g = groups[it["group"]]
+                rows = g["rows_per_split"]
+                assert rows == (it["hn"] * G if it["type"] == 0 else 128)
+                s = (it["slot_row"] - g["base_row"]) // rows
+                assert 0 <= s < g["nsplit"] and it["slot_row"] == g["base_row"] + s * rows
+                slot_owner[it["slot_row"]:it["slot_row"] + rows] += 1
+                group_count[it["group"]] += 1
+            else:
+                assert it["slot_row"] == -1
+    if h.n_groups:
+        assert np.array_equal(group_count[:h.n_groups], groups["nsplit"]) and np.all(groups["nsplit"] > 1)
+        assert np.all(slot_owner[:h.n_partial_rows] == 1)
+        assert h.workspace_bytes >= h.ws_off_ml + 8 * h.n_partial_rows >= 4 * h.n_partial_rows * b.head_dim
+    else:
+        assert h.workspace_bytes == 0
+
+
+@pytest.mark.parametrize("idx,scale", [(1, 1.0), (2, 0.25), (3, 0.1), (4, 0.12), (5, 0.05)])
+def test_planner_covers_scaled_configs(lib, idx, scale):
+    b = synth.config(idx, scale)
+    check_coverage(b, fill(b))
+
+
+def test_planner_covers_full_size_lengths(lib):
+    # full-size length mixes without materialising pools
+    g = np.random.default_rng(0)
+    c3 = g.integers(2048, 16385, 256)
+    b = lengths_only(32, 8, 128, [DECODE] * 256, [1] * 256, c3)
+    d = fill(b)
+    check_coverage(b, d)
+    assert d["header"].n_items >= 4 * 512, "enough items to balance 512 resident workgroups"
+    b = lengths_only(8, 1, 128, [DECODE] * 4 + [PREFILL], [1] * 4 + [4096], [131072, 32768, 70001, 99999, 8192])
+    d = fill(b)
+    check_coverage(b, d)
+    assert d["groups"]["nsplit"].max() <= 64
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 64), (2, 2, 128), (16, 1, 64), (12, 4, 128), (6, 2, 64)])
+def test_planner_head_layouts_and_ragged_chunks(lib, Hq, Hkv, D):
+    b = lengths_only(Hq, Hkv, D, [PREFILL, DECODE, PREFILL, DECODE, PREFILL], [1, 1, 33, 1, 130],
+                     [1, 1, 33, 500, 700])
+    check_coverage(b, fill(b))
+
+
+def test_planner_is_a_function_of_lengths_only(lib):
+    b = synth.config(2, 0.25)
+    p = synth.permute_pages(b, 5)
+    d0, d1 = fill(b), fill(p)
+    assert np.array_equal(d0["items"], d1["items"]) and np.array_equal(d0["groups"], d1["groups"])
+    assert not np.array_equal(d0["bt"], d1["bt"])
+
+
+def test_validation_errors(lib):
+    b = synth.config(1)
+    shape = hb.make_shape(4, 2, 64, b.num_pages)
+    host = np.zeros(1 << 16, np.uint8)
+
+    def code(fn, *a):
+        with pytest.raises(hb.HfxError) as e:
+            fn(*a)
+        return e.value.code
+
+    ok = (b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages)
+    hb.hfx_fill_batch_desc(shape, *ok, host)
+    for bad_shape in [hb.make_shape(4, 3, 64, 8), hb.make_shape(4, 2, 96, 8), hb.make_shape(4, 2, 64, 8, page_size=32),
+                      hb.make_shape(4, 2, 64, 0), hb.make_shape(64, 2, 64, 8), hb.make_shape(12, 6, 64, 8)]:
+        assert code(hb.hfx_fill_batch_desc, bad_shape, *ok, host) == hb.HFX_ERR_SHAPE
+    k = b.kind.copy(); k[0] = 2
+    assert code(hb.hfx_fill_batch_desc, shape, k, *ok[1:], host) == hb.HFX_ERR_KIND
+    q = b.q_len.copy(); q[0] = 2                          # decode with q_len != 1
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, q, *ok[2:], host) == hb.HFX_ERR_LEN
+    c = b.ctx_len.copy(); c[3] = 31                       # context shorter than the chunk
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, b.q_len, c, *ok[3:], host) == hb.HFX_ERR_LEN
+    q = b.q_len.copy(); q[3] = 0
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, q, *ok[2:], host) == hb.HFX_ERR_LEN
+    ip = b.bt_indptr.copy(); ip[1] = 2                    # request 0 needs 3 pages, gets 2
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, b.q_len, b.ctx_len, ip, b.bt_pages, host) == hb.HFX_ERR_PAGES
+    ip = b.bt_indptr.copy(); ip[0] = 1
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, b.q_len, b.ctx_len, ip, b.bt_pages, host) == hb.HFX_ERR_PAGES
+    pg = b.bt_pages.copy(); pg[4] = b.num_pages
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, pg, host) == hb.HFX_ERR_PAGE_ID
+    pg = b.bt_pages.copy(); pg[0] = -1
+    assert code(hb.hfx_fill_batch_desc, shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, pg, host) == hb.HFX_ERR_PAGE_ID
+    assert code(hb.hfx_fill_batch_desc, shape, *ok, np.zeros(64, np.uint8)) == hb.HFX_ERR_BUFSIZE
+    # null pointers, through the raw ABI
+    sz = ctypes.c_size_t()
+    assert lib.hfx_batch_desc_sizes(ctypes.byref(shape), 4, None, None, None, ctypes.byref(sz), ctypes.byref(sz),
+                                    ctypes.byref(sz)) == hb.HFX_ERR_NULL
+    assert lib.hfx_batch_desc_sizes(None, 4, None, None, None, None, None, None) == hb.HFX_ERR_NULL
+    assert lib.hfx_mixed_paged_attention(ctypes.byref(shape), None, None, None, None, None, 0, None, None) == hb.HFX_ERR_NULL
+    # a blob that is not a descriptor
+    junk = np.zeros(4096, np.uint8)
+    assert lib.hfx_mixed_paged_attention(ctypes.byref(shape), 16, 16, junk.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_DESC
+    # shape that differs from the descriptor's
+    other = hb.make_shape(4, 2, 64, b.num_pages + 1)
+    assert lib.hfx_mixed_paged_attention(ctypes.byref(other), 16, 16, host.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_SHAPE
+    # misaligned device pointer
+    assert lib.hfx_mixed_paged_attention(ctypes.byref(shape), 8, 16, host.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_ALIGN
+
+
+def test_extra_reserved_pages_are_ignored(lib):
+    b = synth.make_batch(4, 2, 64, [DECODE, PREFILL], [1, 20], [37, 50], 3, extra_pages_per_request=3)
+    d = fill(b)
+    assert d["header"].n_bt == 3 + 4
+    check_coverage(b, d)
