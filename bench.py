@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of libhfxattn on one MI355X.
+
+A step is one pass of the whole hot path over one scheduled batch: the host builds the batch
+descriptor and uploads it (hfx_build_batch_desc), then one persistent launch executes the mixed
+prefill/decode paged attention (hfx_mixed_paged_attention).  Inputs are resident in HBM before
+the timed region.  The headline workload is the Llama-3-8B-shaped mixed step (64 decodes with
+log-normal contexts + 2 prompt chunks of 512); the decode-heavy and prefill-heavy steps are
+timed as well and reported under "paths" because the metric names all three figures.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def device_pool(torch, batch, seed, copies=1):
+    """N(0,1) bf16 page pool(s) made on the device (for steps whose outputs are not compared here)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    pools = []
+    for _ in range(copies):
+        p = torch.empty(batch.pool_shape(), dtype=torch.bfloat16, device="cuda")
+        p.normal_(generator=g)
+        pools.append(p)
+    return pools
+
+
+def time_launches(torch, hb, step, pools, iters, warmup):
+    """Average duration of one attention launch, HIP events on the launch stream; pools are rotated so that
+    consecutive launches do not find their KV in the last-level cache."""
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        step.pool = pools[i % len(pools)]
+        step.run(stream)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for i in range(iters):
+        step.pool = pools[i % len(pools)]
+        evs[i][0].record(stream)
+        step.run(stream)
+        evs[i][1].record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
+
+
+def path_figures(torch, hb, synth, which, iters, warmup):
+    """Decode-heavy (which=3) or prefill-heavy (which=4) step, attention launches only."""
+    b = synth.config(which, fill_pool=False)
+    if which == 4:
+        b = b.sub_batch(synth.PREFILL)
+    pools = device_pool(torch, b, 1000 + which, copies=1 if which == 3 else 2)
+    step = hb.DeviceStep(b, pool_dev=pools[0])
+    avg, med, best = time_launches(torch, hb, step, pools, iters, warmup)
+    out = {"workload": b.name, "requests": b.num_requests, "query_tokens": b.total_q,
+           "launch_ms_avg": round(avg, 4), "launch_ms_median": round(med, 4), "launch_ms_min": round(best, 4)}
+    if which == 3:
+        byt = b.decode_io_bytes()
+        out.update(bound="hbm", algorithmic_bytes=byt, achieved_GBs=round(byt / avg / 1e6, 1),
+                   frac_of_hbm_peak=round(byt / avg / 1e6 / HBM_PEAK_GBS, 4),
+                   kv_tokens_per_s=round(float(b.ctx_len.sum()) / avg * 1e3, 1))
+    else:
+        fl = b.prefill_flops()
+        out.update(bound="mfma", algorithmic_flops=fl, achieved_TFLOPs=round(fl / avg / 1e9, 1),
+                   frac_of_bf16_mfma_peak=round(fl / avg / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                   tokens_per_s=round(b.total_q / avg * 1e3, 1))
+    del step, pools
+    torch.cuda.empty_cache()
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--pool-copies", type=int, default=4, help="distinct KV pools rotated across steps")
+    ap.add_argument("--no-paths", action="store_true", help="skip the decode-heavy / prefill-heavy steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; there is no sharded path to time (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2508_15919_amd import binding as hb
+    from paper_2508_15919_amd import synth
+
+    hb.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    b = synth.config(2)
+    pools = [torch.from_numpy(b.pool.view(np.int16)).cuda()]
+    for i in range(1, max(1, args.pool_copies)):
+        pools.append(pools[0].clone())
+    ring = [hb.DeviceStep(b, pool_dev=pools[i % len(pools)]) for i in range(max(4, len(pools)))]
+    torch.cuda.synchronize()
+
+    # host cost of building + uploading the descriptor alone
+    t0 = time.perf_counter()
+    for i in range(50):
+        s = ring[i % len(ring)]
+        hb.hfx_build_batch_desc(s.shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, s.host_desc,
+                                s.device_desc, stream)
+        torch.cuda.synchronize()
+    desc_us = (time.perf_counter() - t0) / 50 * 1e6
+
+    def one_step(i, ev=None):
+        s = ring[i % len(ring)]
+        if s.busy is not None:
+            s.busy.synchronize()        # the slot's previous upload and launch have drained
+        hb.hfx_build_batch_desc(s.shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, s.host_desc,
+                                s.device_desc, stream)
+        if ev is not None:
+            ev[0].record(stream)
+        s.run(stream)
+        if ev is not None:
+            ev[1].record(stream)
+        s.busy = torch.cuda.Event()
+        s.busy.record(stream)
+
+    for s in ring:
+        s.busy = None
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    launch_ms = [a.elapsed_time(c) for a, c in evs]
+    launch_avg = sum(launch_ms) / len(launch_ms)
+
+    T = b.total_q
+    alg_bytes = b.decode_io_bytes() + b.prefill_io_bytes()
+    achieved = alg_bytes / launch_avg / 1e6
+    result = {
+        "metric": "mixed-step attention tokens/s", "value": round(T / ms_per_step * 1e3, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2: Llama-3-8B-shaped layer (32 q / 8 kv heads, D 128, page 16), 64 decodes "
+                               "ctx~lognormal(median 1k, max 8k) + 2 prompt chunks of 512 (ctx 512 and 2048)",
+                   "requests": b.num_requests, "query_tokens": T, "decode_kv_tokens": int(b.ctx_len[b.kind == 0].sum()),
+                   "pool_copies_rotated": len(pools), "step": "descriptor build + upload + one persistent launch"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "mixed_attention_kernel<128>", "launch_ms_avg": round(launch_avg, 5),
+                     "algorithmic_bytes": alg_bytes},
+        "launch_only_tokens_per_s": round(T / launch_avg * 1e3, 1),
+        "desc_build_upload_us": round(desc_us, 1),
+        "prefill_flops": b.prefill_flops(),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import hfx_oracle
+        hfx_oracle.attention_batch(synth.config(1))            # load + warm the library
+        t0 = time.perf_counter()
+        ref = hfx_oracle.attention_batch(b)
+        cpu_s = time.perf_counter() - t0
+        got = synth.bf16_bits_to_f64(ring[0].out_bits())
+        err = np.abs(got - ref)
+        result["cpu_baseline"] = {"value": round(T / cpu_s, 2), "unit": "tokens/s", "cores": hfx_oracle.num_threads(),
+                                  "kind": "oracle", "sample": "the whole cfg2 step, one run (%.2f s)" % cpu_s}
+        result["parity_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
+
+    if not args.no_paths:
+        del ring
+        pools.clear()
+        torch.cuda.empty_cache()
+        paths = {}
+        for which, name in ((3, "decode_heavy"), (4, "prefill_heavy")):
+            try:
+                paths[name] = path_figures(torch, hb, synth, which, 30, 5)
+            except Exception as e:  # the headline above stands on its own
+                paths[name] = {"error": repr(e)}
+        result["paths"] = paths
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

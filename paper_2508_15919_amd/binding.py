@@ -197,7 +197,8 @@ ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row
                                                "kb", "ke", "cost", "pad")])
 REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
                                               "pad0", "pad1")])
-GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "pad")])
+GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "type", "req", "h0", "hn",
+                                                "row0")])
 
 
 def parse_desc(host_desc: np.ndarray) -> dict:

@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 3u
+#define HFX_DESC_VERSION 4u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -22,7 +22,7 @@ struct HfxHeader {
   int32_t n_partial_rows;       /* workspace rows: one (query row, q-head) partial each */
   int32_t n_bt;                 /* page ids stored */
   uint32_t off_ctrl, off_req, off_bt, off_items, off_groups;
-  uint32_t n_ctrl;              /* control words: [0] queue head, [1] finished workgroups, [2+i] group i arrivals */
+  uint32_t n_ctrl;              /* control words: [0] queue head, [1] finished workgroups */
   uint64_t total_bytes;
   uint64_t workspace_bytes;
   uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */
@@ -43,16 +43,19 @@ struct HfxReq {
 //  prefill: h0 = first q-head, hn = q-heads covered (1, 2 or 4), row0 = first chunk row,
 //           nrows = rows covered (32 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
 //  group >= 0: the item is one of several splits; its partial goes to workspace rows
-//           [slot_row, slot_row + rows) and the last arrival of the group merges.
+//           [slot_row, slot_row + rows) and the merge kernel combines the group afterwards.
 struct HfxItem {
   int32_t type, req, group, slot_row;
   int32_t h0, hn, row0, nrows;
   int32_t kb, ke, cost, pad;
 };
 
+// One merge group: nsplit partials of rows_per_split rows each, split s at workspace rows
+// base_row + s * rows_per_split.  type/req/h0/hn/row0 are those of the group's items and say
+// which output rows the merged result belongs to.
 struct HfxGroup {
   int32_t nsplit;
-  int32_t base_row;             /* workspace row of split 0 */
+  int32_t base_row;
   int32_t rows_per_split;
-  int32_t pad;
+  int32_t type, req, h0, hn, row0;
 };

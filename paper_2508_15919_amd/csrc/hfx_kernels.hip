@@ -56,13 +56,17 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 }
 
 // ----------------------------------------------------------------------------------------------
-// Split merge: the last split of a group to arrive combines the partial (m, l, acc) rows.
+// Split merge (runs as its own small launch after the persistent kernel, so the partials are
+// ordered by the kernel boundary and no fences or arrival counters are needed): one workgroup
+// per group combines the partial (m, l, acc) rows of its splits,
 //   m* = max m_s,  l* = sum l_s 2^(m_s - m*),  out = sum acc_s 2^(m_s - m*) / l*
-// (m is kept in the base-2 domain throughout.)
+// (m is kept in the base-2 domain throughout), rounds to bf16 and stores.
 // ----------------------------------------------------------------------------------------------
 template <int D>
-__device__ void merge_group(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq,
-                            const HfxGroup& gr) {
+__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(KArgs a) {
+  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
+  const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[blockIdx.x];
+  const HfxReq rq = reinterpret_cast<const HfxReq*>(a.desc + H->off_req)[gr.req];
   const int tid = threadIdx.x;
   const int Hq = H->num_q_heads;
   const int G = Hq / H->num_kv_heads;
@@ -73,12 +77,12 @@ __device__ void merge_group(const KArgs& a, const HfxHeader* H, const HfxItem& i
   for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
     const int row = idx / C4, d4 = (idx % C4) * 4;
     long orow;
-    if (it.type == HFX_ITEM_DECODE) {
-      orow = (long)rq.q_start * Hq + it.h0 * G + row;
+    if (gr.type == HFX_ITEM_DECODE) {
+      orow = (long)rq.q_start * Hq + gr.h0 * G + row;
     } else {
       const int w = row >> 5, nn = row & 31;
-      const int head = it.h0 + w % it.hn;
-      const int qrow = it.row0 + (w / it.hn) * HFX_ROW_BLOCK + nn;
+      const int head = gr.h0 + w % gr.hn;
+      const int qrow = gr.row0 + (w / gr.hn) * HFX_ROW_BLOCK + nn;
       if (qrow >= rq.q_len) continue;
       orow = ((long)rq.q_start + qrow) * Hq + head;
     }
@@ -101,22 +105,6 @@ __device__ void merge_group(const KArgs& a, const HfxHeader* H, const HfxItem& i
   }
 }
 
-// Publishes this item's partial and reports whether this workgroup is the group's last arrival.
-__device__ __forceinline__ bool arrive_last(int* ctrl, int group, int nsplit, int* s_flag) {
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int old = atomicAdd(&ctrl[2 + group], 1);
-    const int last = (old == nsplit - 1);
-    if (last) atomicExch(&ctrl[2 + group], 0);
-    *s_flag = last;
-  }
-  __syncthreads();
-  const bool last = *s_flag != 0;
-  if (last) __threadfence();
-  return last;
-}
-
 // ----------------------------------------------------------------------------------------------
 // Decode item.  One wavefront per kv-head (hn of them), the other 4/hn wavefronts of the
 // workgroup interleave over page pairs.  Per pair (32 tokens) and kv-head a wavefront issues
@@ -133,11 +121,8 @@ struct PairRegs {
 };
 
 template <int D>
-__device__ __forceinline__ void decode_load(PairRegs<D>& r, const __bf16* pool, const int* bt, int last_page,
-                                            int pp, int Hkv, int g, int k_sel, int k_off, int v_sel, int v_off) {
-  const int i0 = pp < last_page ? pp : last_page;
-  const int i1 = pp + 1 < last_page ? pp + 1 : last_page;
-  const int pg0 = bt[i0], pg1 = bt[i1];
+__device__ __forceinline__ void decode_load(PairRegs<D>& r, const __bf16* pool, int pg0, int pg1, int Hkv, int g,
+                                            int k_sel, int k_off, int v_sel, int v_off) {
   constexpr long kBlock = 16 * D;
   const __bf16* kp = pool + (((long)(k_sel ? pg1 : pg0) * Hkv + g) * 2) * kBlock + k_off;
   const __bf16* vp = pool + (((long)(v_sel ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock + v_off;
@@ -193,8 +178,7 @@ __device__ __forceinline__ void decode_compute(PairRegs<D>& r, const bf16x8* qf,
 }
 
 template <int D>
-__device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem,
-                            int* ctrl, int* s_flag) {
+__device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -234,11 +218,26 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
   const int tok_lane = (j >> 1) * 16 + (j & 1) * 8;   // first of this lane's 8 tokens inside the pair
   const int step = 2 * TW;
 
+  // page ids are fetched one pair ahead of the KV loads that need them
+  auto page_id = [&](int i) { return bt[i < last_page ? i : last_page]; };
   PairRegs<D> r0, r1;
   int pp = it.kb + 2 * tw;
-  if (pp < pe) decode_load<D>(r0, a.pool, bt, last_page, pp, Hkv, g, k_sel, k_off, v_sel, v_off);
+  int a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+  if (pp < pe) {
+    a0 = page_id(pp);
+    a1 = page_id(pp + 1);
+    decode_load<D>(r0, a.pool, a0, a1, Hkv, g, k_sel, k_off, v_sel, v_off);
+  }
+  if (pp + step < pe) {
+    b0 = page_id(pp + step);
+    b1 = page_id(pp + step + 1);
+  }
   while (pp < pe) {
-    if (pp + step < pe) decode_load<D>(r1, a.pool, bt, last_page, pp + step, Hkv, g, k_sel, k_off, v_sel, v_off);
+    if (pp + step < pe) decode_load<D>(r1, a.pool, b0, b1, Hkv, g, k_sel, k_off, v_sel, v_off);
+    if (pp + 2 * step < pe) {
+      a0 = page_id(pp + 2 * step);
+      a1 = page_id(pp + 2 * step + 1);
+    }
     {
       const int nv = tend - (pp * HFX_PAGE + tok_lane);
       if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r0, qf, o, m, l, sl2, 8);
@@ -246,7 +245,11 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
     }
     pp += step;
     if (pp >= pe) break;
-    if (pp + step < pe) decode_load<D>(r0, a.pool, bt, last_page, pp + step, Hkv, g, k_sel, k_off, v_sel, v_off);
+    if (pp + step < pe) decode_load<D>(r0, a.pool, a0, a1, Hkv, g, k_sel, k_off, v_sel, v_off);
+    if (pp + 2 * step < pe) {
+      b0 = page_id(pp + 2 * step);
+      b1 = page_id(pp + 2 * step + 1);
+    }
     {
       const int nv = tend - (pp * HFX_PAGE + tok_lane);
       if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r1, qf, o, m, l, sl2, 8);
@@ -304,10 +307,6 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
       }
     }
   }
-  if (it.group >= 0) {
-    const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[it.group];
-    if (arrive_last(ctrl, it.group, gr.nsplit, s_flag)) merge_group<D>(a, H, it, rq, gr);
-  }
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -364,8 +363,7 @@ __device__ __forceinline__ void stage_store(const StageRegs<D>& r, char* smem, i
 }
 
 template <int D>
-__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem,
-                             int* ctrl, int* s_flag) {
+__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -503,35 +501,38 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
       ws_ml[pr * 2] = m;
       ws_ml[pr * 2 + 1] = l;
     }
-    const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[it.group];
-    if (arrive_last(ctrl, it.group, gr.nsplit, s_flag)) merge_group<D>(a, H, it, rq, gr);
   }
 }
 
 // ----------------------------------------------------------------------------------------------
 // The persistent kernel: workgroups pull items in descending modelled cost until the queue is
-// empty.  The queue head and the arrival counters live in the descriptor; the last workgroup
-// to leave restores them to zero so the descriptor can serve the next launch.
+// empty; the fetch of the next item is issued before the current one is processed so that its
+// latency hides behind the item's own loads.  The queue head lives in the descriptor; the last
+// workgroup to leave restores it to zero so the descriptor can serve the next launch.
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(KArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[Smem<D>::kBytes];
-  __shared__ int s_item, s_flag;
+  __shared__ int s_next;
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
   int* ctrl = reinterpret_cast<int*>(a.desc + H->off_ctrl);
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const HfxReq* reqs = reinterpret_cast<const HfxReq*>(a.desc + H->off_req);
   const int n_items = H->n_items;
+  if (threadIdx.x == 0) s_next = atomicAdd(&ctrl[0], 1);
+  __syncthreads();
   for (;;) {
-    __syncthreads();
-    if (threadIdx.x == 0) s_item = atomicAdd(&ctrl[0], 1);
-    __syncthreads();
-    const int idx = uniform(s_item);
+    const int idx = uniform(s_next);
     if (idx >= n_items) break;
+    __syncthreads();   // s_next has been read by all; LDS of the previous item is free
+    int nxt = 0;
+    if (threadIdx.x == 0) nxt = atomicAdd(&ctrl[0], 1);
     const HfxItem it = items[idx];
     const HfxReq rq = reqs[it.req];
-    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem, ctrl, &s_flag);
-    else prefill_item<D>(a, H, it, rq, smem, ctrl, &s_flag);
+    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem);
+    else prefill_item<D>(a, H, it, rq, smem);
+    if (threadIdx.x == 0) s_next = nxt;
+    __syncthreads();
   }
   if (threadIdx.x == 0) {
     const int done = atomicAdd(&ctrl[1], 1);
@@ -570,8 +571,8 @@ hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
 }
 
-hipError_t launch_mixed_attention(int head_dim, int grid, void* desc, const void* q, const void* pool, void* ws,
-                                  void* out, hipStream_t stream) {
+hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, void* desc, const void* q,
+                                  const void* pool, void* ws, void* out, hipStream_t stream) {
   KArgs a;
   a.desc = static_cast<char*>(desc);
   a.q = static_cast<const __bf16*>(q);
@@ -582,6 +583,12 @@ hipError_t launch_mixed_attention(int head_dim, int grid, void* desc, const void
     hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
   else
     hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
+  if (n_groups > 0) {
+    if (head_dim == 128)
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups), dim3(HFX_WG_THREADS), 0, stream, a);
+    else
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups), dim3(HFX_WG_THREADS), 0, stream, a);
+  }
   return hipGetLastError();
 }
 

@@ -115,7 +115,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
         int group = -1;
         if (nsplit > 1) {
           group = (int)P.groups.size();
-          HfxGroup gr = {nsplit, (int32_t)rows, ngc * G, 0};
+          HfxGroup gr = {nsplit, (int32_t)rows, ngc * G, HFX_ITEM_DECODE, r, g0, ngc, 0};
           P.groups.push_back(gr);
         }
         for (int s = 0; s < nsplit; ++s) {
@@ -153,7 +153,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
             int group = -1;
             if (nsplit > 1) {
               group = (int)P.groups.size();
-              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_ROW_BLOCK, 0};
+              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_ROW_BLOCK, HFX_ITEM_PREFILL, r, g * G + hb * hpw, hpw, (int32_t)r0};
               P.groups.push_back(gr);
             }
             for (int64_t s = 0; s < nsplit; ++s) {
@@ -206,7 +206,7 @@ void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
   h->n_groups = (int32_t)P.groups.size();
   h->n_partial_rows = P.n_partial_rows;
   h->n_bt = P.n_bt;
-  h->n_ctrl = (uint32_t)align_up(2 + P.groups.size(), 16);
+  h->n_ctrl = 16;
   uint64_t off = align_up(sizeof(HfxHeader), 256);
   h->off_ctrl = (uint32_t)off;
   off = align_up(off + 4ull * h->n_ctrl, 64);

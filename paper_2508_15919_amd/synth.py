@@ -75,6 +75,9 @@ class StepBatch:
     def total_q(self) -> int:
         return int(self.q_len.sum())
 
+    def pool_shape(self):
+        return (self.num_pages, self.num_kv_heads, 2, PAGE * self.head_dim)
+
     def q_indptr(self) -> np.ndarray:
         out = np.zeros(self.num_requests + 1, dtype=np.int64)
         np.cumsum(self.q_len, out=out[1:])
@@ -186,13 +189,15 @@ def poison_tails(batch: StepBatch) -> None:
 
 def make_batch(num_q_heads: int, num_kv_heads: int, head_dim: int, kind, q_len, ctx_len,
                seed: int, over_provision: float = 1.25, extra_pages_per_request: int = 0,
-               name: str = "", poison: bool = True) -> StepBatch:
+               name: str = "", poison: bool = True, fill_pool: bool = True) -> StepBatch:
     """Build a step over a shuffled, over-provisioned page pool.
 
     Physical ids are the first `need` entries of a seeded permutation of
     [0, num_pages), num_pages = ceil(over_provision * need).  Unused pages and
     last-page tails are NaN when `poison`.  `extra_pages_per_request` appends
-    reserved-but-unused (poisoned) pages to each block table.
+    reserved-but-unused (poisoned) pages to each block table.  With `fill_pool=False`
+    only lengths, block table and Q are made and `pool` is None (the caller fills a
+    device-resident pool of shape pool_shape() itself).
     """
     kind = np.asarray(kind, dtype=np.int32)
     q_len = np.asarray(q_len, dtype=np.int32)
@@ -207,15 +212,17 @@ def make_batch(num_q_heads: int, num_kv_heads: int, head_dim: int, kind, q_len, 
     bt_pages = perm[:need].copy()
     bt_indptr = np.zeros(R + 1, dtype=np.int32)
     bt_indptr[1:] = np.cumsum(per_req)
-    pool = np.empty((num_pages, num_kv_heads, 2, PAGE * head_dim), dtype=np.uint16)
-    pool[...] = BF16_NAN if poison else 0
-    used = np.concatenate([bt_pages[bt_indptr[r]:bt_indptr[r] + npg[r]] for r in range(R)]) if R else bt_pages
-    _fill_pool_normal(pool, used, seed)
+    pool = None
+    if fill_pool:
+        pool = np.empty((num_pages, num_kv_heads, 2, PAGE * head_dim), dtype=np.uint16)
+        pool[...] = BF16_NAN if poison else 0
+        used = np.concatenate([bt_pages[bt_indptr[r]:bt_indptr[r] + npg[r]] for r in range(R)]) if R else bt_pages
+        _fill_pool_normal(pool, used, seed)
     T = int(q_len.sum())
     q = _normal_bf16((seed, 0x71), T * num_q_heads * head_dim).reshape(T, num_q_heads, head_dim)
     b = StepBatch(num_q_heads, num_kv_heads, head_dim, num_pages, kind, q_len, ctx_len,
                   bt_indptr, bt_pages, q, pool, name=name)
-    if poison:
+    if poison and fill_pool:
         poison_tails(b)
     return b
 
@@ -242,7 +249,7 @@ def _scaled(n: int, scale: float, lo: int = 1) -> int:
     return max(lo, int(round(n * scale)))
 
 
-def config(index: int, scale: float = 1.0, seed: int | None = None) -> StepBatch:
+def config(index: int, scale: float = 1.0, seed: int | None = None, fill_pool: bool = True) -> StepBatch:
     """Configuration `index` (1-based).  Seed defaults to index-1."""
     if seed is None:
         seed = index - 1
@@ -250,7 +257,7 @@ def config(index: int, scale: float = 1.0, seed: int | None = None) -> StepBatch
     if index == 1:
         # 3 decodes (context 37/64/129) + 1 prompt chunk of 32 whose context is the chunk itself.
         b = make_batch(4, 2, 64, [DECODE, DECODE, DECODE, PREFILL], [1, 1, 1, 32], [37, 64, 129, 32],
-                       seed, name="cfg1-tiny-mixed")
+                       seed, name="cfg1-tiny-mixed", fill_pool=fill_pool)
     elif index == 2:
         nd = _scaled(64, scale)
         cap = _scaled(8192, scale, 64)
@@ -259,12 +266,12 @@ def config(index: int, scale: float = 1.0, seed: int | None = None) -> StepBatch
         ch = _scaled(512, scale, 16)
         kinds = [DECODE] * nd + [PREFILL, PREFILL]
         b = make_batch(32, 8, 128, kinds, list(np.ones(nd, np.int32)) + [ch, ch],
-                       list(c) + [ch, 4 * ch], seed, name="cfg2-llama8b-mixed")
+                       list(c) + [ch, 4 * ch], seed, name="cfg2-llama8b-mixed", fill_pool=fill_pool)
     elif index == 3:
         nd = _scaled(256, scale)
         lo, hi = _scaled(2048, scale, 16), _scaled(16384, scale, 64)
         c = g.integers(lo, hi + 1, nd).astype(np.int32)
-        b = make_batch(32, 8, 128, [DECODE] * nd, np.ones(nd, np.int32), c, seed, name="cfg3-decode-heavy")
+        b = make_batch(32, 8, 128, [DECODE] * nd, np.ones(nd, np.int32), c, seed, name="cfg3-decode-heavy", fill_pool=fill_pool)
     elif index == 4:
         ch = _scaled(2048, scale, 32)
         nd = _scaled(32, scale, 2)
@@ -274,7 +281,7 @@ def config(index: int, scale: float = 1.0, seed: int | None = None) -> StepBatch
         prior = [0, 2 * ch, 4 * ch, 6 * ch]
         kinds = [PREFILL] * 4 + [DECODE] * nd
         b = make_batch(32, 8, 128, kinds, [ch] * 4 + [1] * nd, [p + ch for p in prior] + list(cd),
-                       seed, name="cfg4-prefill-heavy")
+                       seed, name="cfg4-prefill-heavy", fill_pool=fill_pool)
     elif index == 5:
         nd = _scaled(16, scale, 2)
         lo, hi = _scaled(32768, scale, 64), _scaled(131072, scale, 256)
@@ -283,7 +290,7 @@ def config(index: int, scale: float = 1.0, seed: int | None = None) -> StepBatch
         ctx = _scaled(65536, scale, ch)
         kinds = [DECODE] * nd + [PREFILL]
         b = make_batch(8, 1, 128, kinds, [1] * nd + [ch], list(cd) + [max(ctx, ch)], seed,
-                       name="cfg5-long-context-tp-share")
+                       name="cfg5-long-context-tp-share", fill_pool=fill_pool)
     else:
         raise ValueError("config index must be 1..5")
     b.notes.update(config=index, scale=scale, seed=seed)
