@@ -190,7 +190,8 @@ class DescHeader(ctypes.Structure):
                 ("off_ctrl", ctypes.c_uint32), ("off_req", ctypes.c_uint32), ("off_bt", ctypes.c_uint32),
                 ("off_items", ctypes.c_uint32), ("off_groups", ctypes.c_uint32), ("n_ctrl", ctypes.c_uint32),
                 ("total_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
-                ("ws_off_ml", ctypes.c_uint64), ("reserved", ctypes.c_uint32 * 8)]
+                ("ws_off_ml", ctypes.c_uint64), ("max_group_rows", ctypes.c_int32),
+                ("reserved", ctypes.c_uint32 * 7)]
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",

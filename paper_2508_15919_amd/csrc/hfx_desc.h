@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 4u
+#define HFX_DESC_VERSION 5u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -26,7 +26,8 @@ struct HfxHeader {
   uint64_t total_bytes;
   uint64_t workspace_bytes;
   uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */
-  uint32_t reserved[8];
+  int32_t max_group_rows;       /* largest rows_per_split over the groups */
+  uint32_t reserved[7];
 };
 
 struct HfxReq {

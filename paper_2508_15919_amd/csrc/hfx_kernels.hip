@@ -57,52 +57,94 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 
 // ----------------------------------------------------------------------------------------------
 // Split merge (runs as its own small launch after the persistent kernel, so the partials are
-// ordered by the kernel boundary and no fences or arrival counters are needed): one workgroup
-// per group combines the partial (m, l, acc) rows of its splits,
+// ordered by the kernel boundary and no fences or arrival counters are needed).  Workgroup
+// (group, chunk) combines kMergeRows rows of the group's partials (m, l, acc):
 //   m* = max m_s,  l* = sum l_s 2^(m_s - m*),  out = sum acc_s 2^(m_s - m*) / l*
-// (m is kept in the base-2 domain throughout), rounds to bf16 and stores.
+// (m is kept in the base-2 domain throughout), rounds to bf16 and stores.  The splits of a row
+// are spread over 8 lanes of threads so that their loads are all in flight together.
 // ----------------------------------------------------------------------------------------------
+constexpr int kMergeSplitLanes = 8;
+template <int D>
+struct MergeShape {
+  static constexpr int kCols = D / 4;                                           // float4 columns of a row
+  static constexpr int kRows = HFX_WG_THREADS / (kCols * kMergeSplitLanes);     // rows per workgroup
+};
+
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(KArgs a) {
+  constexpr int C4 = MergeShape<D>::kCols, RB = MergeShape<D>::kRows, SL = kMergeSplitLanes;
+  __shared__ float s_max[RB][SL];
+  __shared__ float s_l[RB][SL];
+  __shared__ f32x4 s_acc[RB][SL][C4];
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
   const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[blockIdx.x];
+  if ((int)blockIdx.y * RB >= gr.rows_per_split) return;
   const HfxReq rq = reinterpret_cast<const HfxReq*>(a.desc + H->off_req)[gr.req];
   const int tid = threadIdx.x;
+  const int col = tid % C4, sl = (tid / C4) % SL, rl = tid / (C4 * SL);
+  const int row = blockIdx.y * RB + rl;
+  const bool row_ok = row < gr.rows_per_split;
   const int Hq = H->num_q_heads;
   const int G = Hq / H->num_kv_heads;
   const float* acc = a.ws;
   const float* ml = reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.ws) + H->ws_off_ml);
   const int rows = gr.rows_per_split, ns = gr.nsplit, base = gr.base_row;
-  constexpr int C4 = D / 4;
-  for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
-    const int row = idx / C4, d4 = (idx % C4) * 4;
-    long orow;
-    if (gr.type == HFX_ITEM_DECODE) {
-      orow = (long)rq.q_start * Hq + gr.h0 * G + row;
-    } else {
-      const int w = row >> 5, nn = row & 31;
-      const int head = gr.h0 + w % gr.hn;
-      const int qrow = gr.row0 + (w / gr.hn) * HFX_ROW_BLOCK + nn;
-      if (qrow >= rq.q_len) continue;
-      orow = ((long)rq.q_start + qrow) * Hq + head;
-    }
-    float mm = NEG_INF;
-    for (int s = 0; s < ns; ++s) mm = fmaxf(mm, ml[((long)base + (long)s * rows + row) * 2]);
-    float ll = 0.f;
-    f32x4 o = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < ns; ++s) {
-      const long pr = (long)base + (long)s * rows + row;
-      const float w = fast_exp2(ml[pr * 2] - mm);
-      ll += ml[pr * 2 + 1] * w;
-      const f32x4 v = *reinterpret_cast<const f32x4*>(acc + pr * D + d4);
-      o += v * w;
-    }
-    const float inv = 1.0f / ll;
-    bf16x4 ob;
+  constexpr int kMax = (64 + SL - 1) / SL;      // the planner never makes more than 64 splits
+  float mv[kMax], lv[kMax];
+  float mloc = NEG_INF;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[e] * inv);
-    *reinterpret_cast<bf16x4*>(a.out + orow * D + d4) = ob;
+  for (int i = 0; i < kMax; ++i) {
+    const int s = sl + i * SL;
+    mv[i] = NEG_INF;
+    lv[i] = 0.f;
+    if (row_ok && s < ns) {
+      const long pr = (long)base + (long)s * rows + row;
+      mv[i] = ml[pr * 2];
+      lv[i] = ml[pr * 2 + 1];
+    }
+    mloc = fmaxf(mloc, mv[i]);
   }
+  if (col == 0) s_max[rl][sl] = mloc;
+  __syncthreads();
+  float mm = NEG_INF;
+#pragma unroll
+  for (int i = 0; i < SL; ++i) mm = fmaxf(mm, s_max[rl][i]);
+  float ll = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < kMax; ++i) {
+    const int s = sl + i * SL;
+    if (row_ok && s < ns) {
+      const long pr = (long)base + (long)s * rows + row;
+      const float w = fast_exp2(mv[i] - mm);
+      ll += lv[i] * w;
+      o += *reinterpret_cast<const f32x4*>(acc + pr * D + col * 4) * w;
+    }
+  }
+  s_acc[rl][sl][col] = o;
+  if (col == 0) s_l[rl][sl] = ll;
+  __syncthreads();
+  if (sl != 0 || !row_ok) return;
+  long orow;
+  if (gr.type == HFX_ITEM_DECODE) {
+    orow = (long)rq.q_start * Hq + gr.h0 * G + row;
+  } else {
+    const int w = row >> 5, nn = row & 31;
+    const int head = gr.h0 + w % gr.hn;
+    const int qrow = gr.row0 + (w / gr.hn) * HFX_ROW_BLOCK + nn;
+    if (qrow >= rq.q_len) return;
+    orow = ((long)rq.q_start + qrow) * Hq + head;
+  }
+#pragma unroll
+  for (int i = 1; i < SL; ++i) {
+    o += s_acc[rl][i][col];
+    ll += s_l[rl][i];
+  }
+  const float inv = 1.0f / ll;
+  bf16x4 ob;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[e] * inv);
+  *reinterpret_cast<bf16x4*>(a.out + orow * D + col * 4) = ob;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -362,6 +404,76 @@ __device__ __forceinline__ void stage_store(const StageRegs<D>& r, char* smem, i
   }
 }
 
+// One 64-key tile for one wavefront.  `m` is the reference exponent (base-2 domain) of the
+// running sums; it is only raised -- and O, l rescaled -- when some row's maximum has grown by
+// more than 2^8 over it, which keeps every weight below 2^8 and makes the rescale rare.
+template <int D, bool MASK>
+__device__ __forceinline__ void prefill_tile(const char* k_lds, const char* v_lds, const bf16x8* qf, f32x16* o,
+                                             float& m, float& l, float sl2, int key0, int pos) {
+  constexpr int KS = Smem<D>::kKStride;
+  constexpr int VR = Smem<D>::kVRegion;
+  f32x16 s[2];
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + u * 32 * KS + kk * 32);
+      if (kk == 0) {
+        f32x16 z;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], z, 0, 0, 0);
+      } else {
+        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[u], 0, 0, 0);
+      }
+    }
+  }
+  // s[u][v] is key key0 + (2u + (v>>3))*16 + (v&7)   (key0 already holds kt + 8j)
+  if (MASK) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = key0 + (2 * u + (v >> 3)) * 16 + (v & 7);
+        s[u][v] = key <= pos ? s[u][v] : NEG_INF;
+      }
+  }
+  float mx = NEG_INF;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) mx = fmaxf(mx, fmaxf(s[u][v], s[u][v + 1]));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;
+  if (__any(mx > m + 8.0f)) {
+    const float mn = fmaxf(m, mx);
+    const float alpha = fast_exp2(m - (mn == NEG_INF ? 0.f : mn));
+    l *= alpha;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) o[b] *= alpha;
+    m = mn;
+  }
+  const float mneg = m == NEG_INF ? 0.f : -m;
+  float ps = 0.f;
+  bf16x8 pb[4];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float pv = fast_exp2(__builtin_fmaf(s[u][v], sl2, mneg));
+      ps += pv;
+      pb[2 * u + (v >> 3)][v & 7] = (__bf16)pv;
+    }
+  l += ps;
+#pragma unroll
+  for (int sp = 0; sp < 4; ++sp) {
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) {
+      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_lds + sp * 2 * VR + b * 32 * 16);
+      o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sp], o[b], 0, 0, 0);
+    }
+  }
+}
+
 template <int D>
 __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
   const int tid = threadIdx.x;
@@ -413,60 +525,10 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
       stage_load<D>(st, a.pool, bt, last_page, kt + HFX_KEY_TILE, rq.ctx_len, Hkv, g, tid);
     if (kt >= wave_kend) continue;
 
-    f32x16 s[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[u][v] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + u * 32 * KS + kk * 32);
-        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[u], 0, 0, 0);
-      }
-    }
-    // s[u][v] is key kt + (2u + (v>>3))*16 + j*8 + (v&7)
-    const bool need_mask = kt + HFX_KEY_TILE - 1 > wave_pmin;
-    float mx = NEG_INF;
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = s[u][v] * sl2;
-        if (need_mask) {
-          const int key = kt + (2 * u + (v >> 3)) * 16 + j * 8 + (v & 7);
-          x = key <= pos ? x : NEG_INF;
-        }
-        s[u][v] = x;
-        mx = fmaxf(mx, x);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);
-    const float ms = mn == NEG_INF ? 0.f : mn;
-    const float alpha = fast_exp2(m - ms);
-    float ps = 0.f;
-    bf16x8 pb[4];
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float pv = fast_exp2(s[u][v] - ms);
-        ps += pv;
-        pb[2 * u + (v >> 3)][v & 7] = (__bf16)pv;
-      }
-    l = l * alpha + ps;
-    m = mn;
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b) o[b] *= alpha;
-#pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
-#pragma unroll
-      for (int b = 0; b < D / 32; ++b) {
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_lds + sp * 2 * VR + b * 32 * 16);
-        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sp], o[b], 0, 0, 0);
-      }
-    }
+    if (kt + HFX_KEY_TILE - 1 > wave_pmin)
+      prefill_tile<D, true>(k_lds, v_lds, qf, o, m, l, sl2, kt + j * 8, pos);
+    else
+      prefill_tile<D, false>(k_lds, v_lds, qf, o, m, l, sl2, 0, 0);
   }
   l += __shfl_xor(l, 32, 64);
 
@@ -571,8 +633,8 @@ hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
 }
 
-hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, void* desc, const void* q,
-                                  const void* pool, void* ws, void* out, hipStream_t stream) {
+hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, int max_group_rows, void* desc,
+                                  const void* q, const void* pool, void* ws, void* out, hipStream_t stream) {
   KArgs a;
   a.desc = static_cast<char*>(desc);
   a.q = static_cast<const __bf16*>(q);
@@ -584,10 +646,13 @@ hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, void* de
   else
     hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
   if (n_groups > 0) {
-    if (head_dim == 128)
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups), dim3(HFX_WG_THREADS), 0, stream, a);
-    else
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups), dim3(HFX_WG_THREADS), 0, stream, a);
+    if (head_dim == 128) {
+      const int chunks = (max_group_rows + MergeShape<128>::kRows - 1) / MergeShape<128>::kRows;
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, a);
+    } else {
+      const int chunks = (max_group_rows + MergeShape<64>::kRows - 1) / MergeShape<64>::kRows;
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, a);
+    }
   }
   return hipGetLastError();
 }

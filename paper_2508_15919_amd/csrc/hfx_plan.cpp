@@ -19,7 +19,8 @@ static const double kMinItemNs = 16000.0;
 static const int kMinDecodeTokens = 128;
 static const int kMinPrefillKeys = 256;
 static const int kMaxSplits = 64;
-static const int kItemsPerWg = 8;
+static const int kDecodeItemsPerWg = 8;    // decode partials are small (rows of D + 2 floats per q-head)
+static const int kPrefillItemsPerWg = 2;   // prefill partials are 128 rows: split only where balance needs it
 
 static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
 static int q_heads_per_item(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1); }
@@ -91,7 +92,8 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   }
   P.total_q = (int32_t)T;
   P.n_bt = (int32_t)nbt;
-  const double cap_ns = std::max(total_ns / (HFX_PLAN_WGS * kItemsPerWg), kMinItemNs);
+  const double cap_ns = std::max(total_ns / (HFX_PLAN_WGS * kDecodeItemsPerWg), kMinItemNs);
+  const double cap_prefill_ns = std::max(total_ns / (HFX_PLAN_WGS * kPrefillItemsPerWg), kMinItemNs);
 
   int64_t rows = 0;
   const int ngc = kv_heads_per_item(Hkv);
@@ -143,7 +145,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
         const int64_t kmax = p + r1;
         const int64_t ntiles = (kmax + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
         const double ns_all = 4.0 * D * hpw * (double)pairs_in(p, r0, r1, 0, kmax) / kPrefillFlopsPerNs;
-        int64_t nsplit = (int64_t)std::ceil(ns_all / cap_ns);
+        int64_t nsplit = (int64_t)std::ceil(ns_all / cap_prefill_ns);
         nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kMaxSplits));
         int64_t tiles_per = (ntiles + nsplit - 1) / nsplit;
         tiles_per = std::max<int64_t>(tiles_per, kMinPrefillKeys / HFX_KEY_TILE);
@@ -207,6 +209,8 @@ void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
   h->n_partial_rows = P.n_partial_rows;
   h->n_bt = P.n_bt;
   h->n_ctrl = 16;
+  h->max_group_rows = 0;
+  for (const HfxGroup& g : P.groups) h->max_group_rows = std::max(h->max_group_rows, g.rows_per_split);
   uint64_t off = align_up(sizeof(HfxHeader), 256);
   h->off_ctrl = (uint32_t)off;
   off = align_up(off + 4ull * h->n_ctrl, 64);
