@@ -29,15 +29,13 @@ struct KArgs {
 
 template <int D>
 struct Smem {
-  // prefill: K tile, token-major rows padded by 16 B; V tile, [page][token half][d][8 tokens]
+  // prefill: two K tiles (64 keys each), token-major rows padded by 16 B to spread the banks
   static constexpr int kKStride = D * 2 + 16;
   static constexpr int kKBytes = HFX_KEY_TILE * kKStride;
-  static constexpr int kVRegion = D * 16 + 128;
-  static constexpr int kVBytes = 8 * kVRegion;
   // decode: per-wavefront partial rows [4][16][D + 4] floats
   static constexpr int kPartStride = D + 4;
   static constexpr int kPartBytes = 4 * 16 * kPartStride * 4;
-  static constexpr int kBytes = (kKBytes + kVBytes) > kPartBytes ? (kKBytes + kVBytes) : kPartBytes;
+  static constexpr int kBytes = 2 * kKBytes > kPartBytes ? 2 * kKBytes : kPartBytes;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -129,9 +127,9 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(KArgs a) {
   if (gr.type == HFX_ITEM_DECODE) {
     orow = (long)rq.q_start * Hq + gr.h0 * G + row;
   } else {
-    const int w = row >> 5, nn = row & 31;
+    const int w = row / HFX_WAVE_ROWS, nn = row % HFX_WAVE_ROWS;
     const int head = gr.h0 + w % gr.hn;
-    const int qrow = gr.row0 + (w / gr.hn) * HFX_ROW_BLOCK + nn;
+    const int qrow = gr.row0 + (w / gr.hn) * HFX_WAVE_ROWS + nn;
     if (qrow >= rq.q_len) return;
     orow = ((long)rq.q_start + qrow) * Hq + head;
   }
@@ -352,97 +350,85 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
 }
 
 // ----------------------------------------------------------------------------------------------
-// Prefill item.  Four wavefronts, each owning a block of 32 chunk rows of one q-head; all four
-// share the kv-head, so one K/V tile (64 keys = 4 pages) staged in LDS serves them all.
-//   S^T[key][row]  = K[key][:] . Q[row][:]              (MFMA 32x32x16, A = K rows from LDS, B = Q^T in registers)
-//   O^T[d][row]   += V^T[d][key] . P^T[key][row]         (A = V^T rows from LDS, B = P^T from the score registers)
-// Each lane owns one query row (column of S^T and O^T), so the running max / sum / rescale are
-// lane-local up to one exchange with lane ^ 32.  The K rows of a score tile are taken in the
-// order that leaves every lane with 8 consecutive keys of one page per 16-key MFMA step.
+// Prefill item.  Four wavefronts, each owning 64 chunk rows (two MFMA row blocks) of one
+// q-head; all four share the kv-head.  Operand traffic, not MFMA issue, is what bounds this
+// loop on CDNA4, so every operand fetched is used twice and the two contractions take their
+// tiles over two different paths:
+//   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows read from an LDS tile (staged once per
+//                                                 workgroup, double buffered), B = Q^T in registers;
+//   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows loaded straight from the page pool
+//                                                 (a dimension-major V block already has the MFMA
+//                                                 operand layout), B = P^T from the score registers.
+// Each lane owns one query row per row block (a column of S^T and O^T), so the running maximum,
+// sum and rescale are lane-local up to one exchange with lane ^ 32.  The K rows of a score tile
+// are taken in the order that leaves every lane with 8 consecutive keys of one page per 16-key
+// MFMA step.
 // ----------------------------------------------------------------------------------------------
 template <int D>
-struct StageRegs {
-  static constexpr int kChunks = 4 * 2 * D;   // 16-byte chunks of K (or of V) per 64-key tile
+struct KStage {
+  static constexpr int kChunks = 4 * 2 * D;   // 16-byte chunks of K per 64-key tile
   static constexpr int kPer = kChunks / HFX_WG_THREADS;
-  bf16x8 k[kPer], v[kPer];
+  bf16x8 k[kPer];
 };
 
+struct TilePages {
+  int pg[4];
+};
+
+__device__ __forceinline__ TilePages tile_pages(const int* bt, int last_page, int kt) {
+  TilePages t;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int lp = kt / HFX_PAGE + s;
+    t.pg[s] = bt[lp < last_page ? lp : last_page];
+  }
+  return t;
+}
+
 template <int D>
-__device__ __forceinline__ void stage_load(StageRegs<D>& r, const __bf16* pool, const int* bt, int last_page,
-                                           int kt, int ctx, int Hkv, int g, int tid) {
+__device__ __forceinline__ void k_stage_load(KStage<D>& r, const __bf16* pool, const TilePages& tp, int Hkv, int g,
+                                             int tid) {
   constexpr int CH = 2 * D;   // 16-byte chunks per (page, head) K block
   constexpr long kBlock = 16 * D;
 #pragma unroll
-  for (int i = 0; i < StageRegs<D>::kPer; ++i) {
+  for (int i = 0; i < KStage<D>::kPer; ++i) {
     const int c = i * HFX_WG_THREADS + tid;
     const int pi = c / CH, w = c % CH;
-    const int lp = kt / HFX_PAGE + pi;
-    const int pg = bt[lp < last_page ? lp : last_page];
-    const __bf16* base = pool + (((long)pg * Hkv + g) * 2) * kBlock;
-    r.k[i] = ld16(base + w * 8);
-    bf16x8 vv = ld16(base + kBlock + w * 8);
-    if (kt + HFX_KEY_TILE > ctx) vv = keep_first(vv, ctx - (lp * HFX_PAGE + (w & 1) * 8));
-    r.v[i] = vv;
+    const int pg = pi == 0 ? tp.pg[0] : pi == 1 ? tp.pg[1] : pi == 2 ? tp.pg[2] : tp.pg[3];
+    r.k[i] = ld16(pool + (((long)pg * Hkv + g) * 2) * kBlock + w * 8);
   }
 }
 
 template <int D>
-__device__ __forceinline__ void stage_store(const StageRegs<D>& r, char* smem, int tid) {
+__device__ __forceinline__ void k_stage_store(const KStage<D>& r, char* kbuf, int tid) {
   constexpr int CH = 2 * D;
   constexpr int KS = Smem<D>::kKStride;
-  constexpr int VR = Smem<D>::kVRegion;
-  char* vbase = smem + Smem<D>::kKBytes;
 #pragma unroll
-  for (int i = 0; i < StageRegs<D>::kPer; ++i) {
+  for (int i = 0; i < KStage<D>::kPer; ++i) {
     const int c = i * HFX_WG_THREADS + tid;
     const int pi = c / CH, w = c % CH;
-    // K chunk w: token w / (D/8), 16-byte column w % (D/8)
-    const int tok = w / (D / 8), col = w % (D / 8);
-    *reinterpret_cast<bf16x8*>(smem + (pi * 16 + tok) * KS + col * 16) = r.k[i];
-    // V chunk w: dimension w >> 1, token half w & 1
-    *reinterpret_cast<bf16x8*>(vbase + (pi * 2 + (w & 1)) * VR + (w >> 1) * 16) = r.v[i];
+    const int tok = w / (D / 8), col = w % (D / 8);   // K chunk w: token, 16-byte column
+    *reinterpret_cast<bf16x8*>(kbuf + (pi * 16 + tok) * KS + col * 16) = r.k[i];
   }
 }
 
-// One 64-key tile for one wavefront.  `m` is the reference exponent (base-2 domain) of the
-// running sums; it is only raised -- and O, l rescaled -- when some row's maximum has grown by
-// more than 2^8 over it, which keeps every weight below 2^8 and makes the rescale rare.
+// Softmax of one row block's 32 scores (one MFMA result tile).  `m` is the reference exponent
+// (base-2 domain) of the running sums; it is only raised -- and O, l rescaled -- when some row's
+// maximum has grown by more than 2^8 over it, which keeps every weight below 2^8 and makes the
+// rescale rare.  s[v] is key key0 + (v>>3)*16 + (v&7)   (key0 already holds the lane's 8j).
 template <int D, bool MASK>
-__device__ __forceinline__ void prefill_tile(const char* k_lds, const char* v_lds, const bf16x8* qf, f32x16* o,
-                                             float& m, float& l, float sl2, int key0, int pos) {
-  constexpr int KS = Smem<D>::kKStride;
-  constexpr int VR = Smem<D>::kVRegion;
-  f32x16 s[2];
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + u * 32 * KS + kk * 32);
-      if (kk == 0) {
-        f32x16 z;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) z[v] = 0.f;
-        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], z, 0, 0, 0);
-      } else {
-        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[u], 0, 0, 0);
-      }
-    }
-  }
-  // s[u][v] is key key0 + (2u + (v>>3))*16 + (v&7)   (key0 already holds kt + 8j)
+__device__ __forceinline__ void softmax_block(f32x16& s, f32x16* o, float& m, float& l, bf16x8* pb, float sl2,
+                                              int key0, int pos) {
   if (MASK) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = key0 + (2 * u + (v >> 3)) * 16 + (v & 7);
-        s[u][v] = key <= pos ? s[u][v] : NEG_INF;
-      }
+    for (int v = 0; v < 16; ++v) {
+      const int key = key0 + (v >> 3) * 16 + (v & 7);
+      s[v] = key <= pos ? s[v] : NEG_INF;
+    }
   }
-  float mx = NEG_INF;
+  float mx = fmaxf(s[0], s[1]);
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int v = 0; v < 16; v += 2) mx = fmaxf(mx, fmaxf(s[u][v], s[u][v + 1]));
+  for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(s[v], s[v + 1]));
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;
   if (__any(mx > m + 8.0f)) {
     const float mn = fmaxf(m, mx);
@@ -454,24 +440,93 @@ __device__ __forceinline__ void prefill_tile(const char* k_lds, const char* v_ld
   }
   const float mneg = m == NEG_INF ? 0.f : -m;
   float ps = 0.f;
-  bf16x8 pb[4];
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float pv = fast_exp2(__builtin_fmaf(s[u][v], sl2, mneg));
-      ps += pv;
-      pb[2 * u + (v >> 3)][v & 7] = (__bf16)pv;
-    }
+  for (int v = 0; v < 16; ++v) {
+    const float pv = fast_exp2(__builtin_fmaf(s[v], sl2, mneg));
+    ps += pv;
+    pb[v >> 3][v & 7] = (__bf16)pv;
+  }
   l += ps;
+}
+
+// Per-wavefront state of a prefill item that lives across key tiles.
+template <int D>
+struct PrefillWave {
+  f32x16 o[2][D / 32];     // O^T accumulators, [row block][32-dimension block]
+  bf16x8 qf[2][D / 16];    // Q^T operand fragments
+  float m[2], l[2];        // reference exponent and running sum per row block
+  int pos[2];              // last key each of this lane's two rows may see
+};
+
+// One 64-key tile: issue the next tile's K loads, run the two 32-key halves from the current LDS
+// buffer, then publish the next K tile into the other buffer.  MASK selects the variant that
+// applies the causal / context-end masks (tiles that reach past some row's horizon).
+template <int D, bool MASK>
+__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, KStage<D>& st, TilePages& tp, const __bf16* pool,
+                                             const int* bt, int last_page, char* smem, int& buf, int kt, int ke,
+                                             int wave_kend, int ctx_len, int Hkv, int g, int k_lane, int v_lane,
+                                             int j, float sl2, int tid) {
+  constexpr int KS = Smem<D>::kKStride;
+  constexpr long kBlock = 16 * D;
+  const bool more = kt + HFX_KEY_TILE < ke;
+  const TilePages cur = tp;
+  if (more) {
+    tp = tile_pages(bt, last_page, kt + HFX_KEY_TILE);
+    k_stage_load<D>(st, pool, tp, Hkv, g, tid);
+  }
+  if (kt < wave_kend) {
+    const char* kb = smem + buf * Smem<D>::kKBytes + k_lane;
 #pragma unroll
-  for (int sp = 0; sp < 4; ++sp) {
+    for (int u = 0; u < 2; ++u) {
+      // V^T fragments of this half, straight from the pool: vf[sp][b] = rows 32b+n, keys 8j.. of page 2u+sp
+      bf16x8 vf[2][D / 32];
 #pragma unroll
-    for (int b = 0; b < D / 32; ++b) {
-      const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v_lds + sp * 2 * VR + b * 32 * 16);
-      o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sp], o[b], 0, 0, 0);
+      for (int sp = 0; sp < 2; ++sp) {
+        const __bf16* vb = pool + (((long)cur.pg[2 * u + sp] * Hkv + g) * 2 + 1) * kBlock + v_lane;
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b) vf[sp][b] = ld16(vb + b * 512);
+      }
+      f32x16 s[2];
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + u * 32 * KS + kk * 32);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          if (kk == 0) {
+            f32x16 z;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[rb][kk], z, 0, 0, 0);
+          } else {
+            s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[rb][kk], s[rb], 0, 0, 0);
+          }
+        }
+      }
+      if (MASK) {   // a tile that runs past the context: unused V slots may hold anything
+        if (kt + HFX_KEY_TILE > ctx_len) {
+#pragma unroll
+          for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b)
+              vf[sp][b] = keep_first(vf[sp][b], ctx_len - (kt + (2 * u + sp) * 16 + j * 8));
+        }
+      }
+      bf16x8 pb[2][2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+        softmax_block<D, MASK>(s[rb], w.o[rb], w.m[rb], w.l[rb], pb[rb], sl2, kt + u * 32 + j * 8, w.pos[rb]);
+#pragma unroll
+      for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+            w.o[rb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[sp][b], pb[rb][sp], w.o[rb][b], 0, 0, 0);
     }
   }
+  if (more) k_stage_store<D>(st, smem + (buf ^ 1) * Smem<D>::kKBytes, tid);
+  __syncthreads();
+  buf ^= 1;
 }
 
 template <int D>
@@ -483,85 +538,89 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
   const int G = Hq / Hkv;
   const int head = it.h0 + wave % it.hn;
   const int g = it.h0 / G;
-  const int r0 = it.row0 + (wave / it.hn) * HFX_ROW_BLOCK;
+  const int r0 = it.row0 + (wave / it.hn) * HFX_WAVE_ROWS;
   const int n = lane & 31, j = lane >> 5;
   const int p = rq.ctx_len - rq.q_len;
-  const int qrow = r0 + n;
-  const int qrow_c = qrow < rq.q_len ? qrow : rq.q_len - 1;
-  const int pos = p + qrow_c;                                   // last key this row may see
-  const int wave_kend = r0 < rq.q_len ? p + min(r0 + HFX_ROW_BLOCK, rq.q_len) : 0;   // keys >= this: nothing to do
+  const int wave_kend = r0 < rq.q_len ? p + min(r0 + HFX_WAVE_ROWS, rq.q_len) : 0;   // keys >= this: nothing to do
   const int wave_pmin = p + r0;                                 // keys <= this are visible to every row
   const float sl2 = H->softmax_scale * 1.4426950408889634f;
 
-  bf16x8 qf[D / 16];
-  {
-    const __bf16* qp = a.q + (((long)rq.q_start + qrow_c) * Hq + head) * D + j * 8;
+  PrefillWave<D> w;
+  int qrow[2];
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) qf[kk] = ld16(qp + kk * 16);
+  for (int rb = 0; rb < 2; ++rb) {
+    qrow[rb] = r0 + rb * 32 + n;
+    const int qc = qrow[rb] < rq.q_len ? qrow[rb] : rq.q_len - 1;
+    w.pos[rb] = p + qc;
+    const __bf16* qp = a.q + (((long)rq.q_start + qc) * Hq + head) * D + j * 8;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) w.qf[rb][kk] = ld16(qp + kk * 16);
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) w.o[rb][b][v] = 0.f;
+    w.m[rb] = NEG_INF;
+    w.l[rb] = 0.f;
   }
-  f32x16 o[D / 32];
-#pragma unroll
-  for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[b][v] = 0.f;
-  float m = NEG_INF, l = 0.f;
 
   const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
   const int last_page = rq.n_pages - 1;
-  constexpr int KS = Smem<D>::kKStride;
-  constexpr int VR = Smem<D>::kVRegion;
   // LDS row of this lane's K row in score sub-tile 0 (sub-tile u adds 32 rows)
   const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
-  const char* k_lds = smem + krow * KS + j * 16;
-  const char* v_lds = smem + Smem<D>::kKBytes + j * VR + n * 16;
+  const int k_lane = krow * Smem<D>::kKStride + j * 16;
+  const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
 
-  StageRegs<D> st;
-  stage_load<D>(st, a.pool, bt, last_page, it.kb, rq.ctx_len, Hkv, g, tid);
-  for (int kt = it.kb; kt < it.ke; kt += HFX_KEY_TILE) {
-    __syncthreads();
-    stage_store<D>(st, smem, tid);
-    __syncthreads();
-    if (kt + HFX_KEY_TILE < it.ke)
-      stage_load<D>(st, a.pool, bt, last_page, kt + HFX_KEY_TILE, rq.ctx_len, Hkv, g, tid);
-    if (kt >= wave_kend) continue;
+  KStage<D> st;
+  TilePages tp = tile_pages(bt, last_page, it.kb);
+  k_stage_load<D>(st, a.pool, tp, Hkv, g, tid);
+  k_stage_store<D>(st, smem, tid);
+  __syncthreads();
+  int buf = 0;
+  // tiles whose every key every row of this wavefront sees come first and need no masks
+  int kt_mask = ((max(wave_pmin - (HFX_KEY_TILE - 2), 0) + HFX_KEY_TILE - 1) / HFX_KEY_TILE) * HFX_KEY_TILE;
+  kt_mask = min(max(kt_mask, it.kb), it.ke);
+  int kt = it.kb;
+  for (; kt < kt_mask; kt += HFX_KEY_TILE)
+    prefill_tile<D, false>(w, st, tp, a.pool, bt, last_page, smem, buf, kt, it.ke, wave_kend, rq.ctx_len, Hkv, g,
+                           k_lane, v_lane, j, sl2, tid);
+  for (; kt < it.ke; kt += HFX_KEY_TILE)
+    prefill_tile<D, true>(w, st, tp, a.pool, bt, last_page, smem, buf, kt, it.ke, wave_kend, rq.ctx_len, Hkv, g,
+                          k_lane, v_lane, j, sl2, tid);
 
-    if (kt + HFX_KEY_TILE - 1 > wave_pmin)
-      prefill_tile<D, true>(k_lds, v_lds, qf, o, m, l, sl2, kt + j * 8, pos);
-    else
-      prefill_tile<D, false>(k_lds, v_lds, qf, o, m, l, sl2, 0, 0);
-  }
-  l += __shfl_xor(l, 32, 64);
-
-  // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
-  if (it.group < 0) {
-    if (qrow < rq.q_len) {
-      const float inv = 1.0f / l;
-      __bf16* dst = a.out + (((long)rq.q_start + qrow) * Hq + head) * D + 4 * j;
+  // o[rb][b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row qrow[rb]
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const float lsum = w.l[rb] + __shfl_xor(w.l[rb], 32, 64);
+    if (it.group < 0) {
+      if (qrow[rb] < rq.q_len) {
+        const float inv = 1.0f / lsum;
+        __bf16* dst = a.out + (((long)rq.q_start + qrow[rb]) * Hq + head) * D + 4 * j;
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 ob;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(w.o[rb][b][q4 * 4 + e] * inv);
+            *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
+          }
+      }
+    } else {
+      float* ws_acc = a.ws;
+      float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
+      const long pr = (long)it.slot_row + wave * HFX_WAVE_ROWS + rb * 32 + n;
+      float* dst = ws_acc + pr * D + 4 * j;
 #pragma unroll
       for (int b = 0; b < D / 32; ++b)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          bf16x4 ob;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[b][q4 * 4 + e] * inv);
-          *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
+          f32x4 t = {w.o[rb][b][q4 * 4], w.o[rb][b][q4 * 4 + 1], w.o[rb][b][q4 * 4 + 2], w.o[rb][b][q4 * 4 + 3]};
+          *reinterpret_cast<f32x4*>(dst + b * 32 + q4 * 8) = t;
         }
-    }
-  } else {
-    float* ws_acc = a.ws;
-    float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
-    const long pr = (long)it.slot_row + wave * HFX_ROW_BLOCK + n;
-    float* dst = ws_acc + pr * D + 4 * j;
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        f32x4 t = {o[b][q4 * 4], o[b][q4 * 4 + 1], o[b][q4 * 4 + 2], o[b][q4 * 4 + 3]};
-        *reinterpret_cast<f32x4*>(dst + b * 32 + q4 * 8) = t;
+      if (j == 0) {
+        ws_ml[pr * 2] = w.m[rb];
+        ws_ml[pr * 2 + 1] = lsum;
       }
-    if (j == 0) {
-      ws_ml[pr * 2] = m;
-      ws_ml[pr * 2 + 1] = l;
     }
   }
 }
@@ -573,7 +632,7 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
 // workgroup to leave restores it to zero so the descriptor can serve the next launch.
 // ----------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(KArgs a) {
+__global__ __launch_bounds__(HFX_WG_THREADS, 1) void mixed_attention_kernel(KArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[Smem<D>::kBytes];
   __shared__ int s_next;
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);

@@ -20,7 +20,7 @@ static const int kMinDecodeTokens = 128;
 static const int kMinPrefillKeys = 256;
 static const int kMaxSplits = 64;
 static const int kDecodeItemsPerWg = 8;    // decode partials are small (rows of D + 2 floats per q-head)
-static const int kPrefillItemsPerWg = 2;   // prefill partials are 128 rows: split only where balance needs it
+static const int kPrefillItemsPerWg = 2;   // prefill partials are 256 rows: split only where balance needs it
 
 static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
 static int q_heads_per_item(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1); }
@@ -98,7 +98,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   int64_t rows = 0;
   const int ngc = kv_heads_per_item(Hkv);
   const int hpw = q_heads_per_item(G);
-  const int rows_wg = HFX_ROW_BLOCK * (4 / hpw);
+  const int rows_wg = HFX_WAVE_ROWS * (4 / hpw);
   for (int r = 0; r < R; ++r) {
     const HfxReq& q = P.reqs[(size_t)r];
     if (q.kind == HFX_DECODE) {
@@ -155,7 +155,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
             int group = -1;
             if (nsplit > 1) {
               group = (int)P.groups.size();
-              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_ROW_BLOCK, HFX_ITEM_PREFILL, r, g * G + hb * hpw, hpw, (int32_t)r0};
+              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_WAVE_ROWS, HFX_ITEM_PREFILL, r, g * G + hb * hpw, hpw, (int32_t)r0};
               P.groups.push_back(gr);
             }
             for (int64_t s = 0; s < nsplit; ++s) {
@@ -164,7 +164,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
               it.type = HFX_ITEM_PREFILL;
               it.req = r;
               it.group = group;
-              it.slot_row = (nsplit > 1) ? (int32_t)(rows + s * 4 * HFX_ROW_BLOCK) : -1;
+              it.slot_row = (nsplit > 1) ? (int32_t)(rows + s * 4 * HFX_WAVE_ROWS) : -1;
               it.h0 = g * G + hb * hpw;
               it.hn = hpw;
               it.row0 = (int32_t)r0;
@@ -174,7 +174,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
               it.cost = clamp_cost(4.0 * D * hpw * (double)pairs_in(p, r0, r1, it.kb, it.ke) / kPrefillFlopsPerNs + 3000.0);
               P.items.push_back(it);
             }
-            if (nsplit > 1) rows += nsplit * 4 * HFX_ROW_BLOCK;
+            if (nsplit > 1) rows += nsplit * 4 * HFX_WAVE_ROWS;
           }
       }
     }
