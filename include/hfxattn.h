@@ -64,10 +64,13 @@ typedef struct {
  *
  *   pool[num_pages][Hkv][2][16 * D]
  *
- * For page P and kv-head g the first 16*D elements are the keys, token-major:
- * K[slot][d] at (slot * D + d).  The second 16*D elements are the values,
- * dimension-major: V[slot][d] at (d * 16 + slot).  Logical token t of a
- * request lives in page bt_pages[bt_indptr[r] + t / 16] at slot t % 16
+ * For page P and kv-head g the first 16*D elements are the keys, blocked by
+ * groups of 16 dimensions: K[slot][d] at ((d / 16) * 16 + slot) * 16 + d % 16
+ * (for each 16-dimension group, the 16 slots' 32-byte pieces are contiguous).
+ * The second 16*D elements are the values, dimension-major: V[slot][d] at
+ * (d * 16 + slot).  Both are the order in which the matrix cores consume the
+ * operands, so a page streams into them without a transpose.  Logical token t
+ * of a request lives in page bt_pages[bt_indptr[r] + t / 16] at slot t % 16
  * (block-managed cache, Sections 3.3.3 and 3.4).  Slots at or past ctx_len in
  * a request's last page, and pages no block table names, may hold anything
  * (including NaN) and never influence a result.

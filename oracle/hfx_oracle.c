@@ -22,8 +22,10 @@
  * head) units over cores and changes no arithmetic inside a unit.
  *
  * Pool layout read here: page-major, then kv-head, then K block, then V block;
- * a K block is token-major (16 rows of D), a V block dimension-major (D rows
- * of 16).  Token t of request r: page bt_pages[bt_indptr[r] + t/16], slot t%16.
+ * a K block holds, for each group of 16 dimensions in turn, the 16 slots' 16
+ * values (element (slot, d) at ((d/16)*16 + slot)*16 + d%16); a V block is
+ * dimension-major (D rows of 16 slots).  Token t of request r: page
+ * bt_pages[bt_indptr[r] + t/16], slot t%16.
  *
  * Pins (tests/test_oracle_pins.py): dense brute force on un-paged KV written
  * in numpy, torch's scaled_dot_product_attention in float64, single-token
@@ -62,10 +64,13 @@ static size_t block_base(const orc_ctx* c, long page, int g, int which) {
   return (((size_t)page * (size_t)c->Hkv + (size_t)g) * 2u + (size_t)which) * blk;
 }
 
+/* element offset of (slot, d) inside a K block */
+static size_t k_offset(int slot, int d) { return ((size_t)(d / 16) * ORC_PAGE + (size_t)slot) * 16u + (size_t)(d % 16); }
+
 static double key_at(const orc_ctx* c, int r, long t, int g, int d) {
   long page = c->bt_pages[c->bt_indptr[r] + t / ORC_PAGE];
   int slot = (int)(t % ORC_PAGE);
-  return widen(c->pool[block_base(c, page, g, 0) + (size_t)slot * c->D + d]);
+  return widen(c->pool[block_base(c, page, g, 0) + k_offset(slot, d)]);
 }
 
 static double value_at(const orc_ctx* c, int r, long t, int g, int d) {
@@ -100,7 +105,7 @@ static void one_unit(const orc_ctx* c, double scale, int r, long n, int h, const
 static int check_inputs(int Hq, int Hkv, int D, long num_pages, int R, const int32_t* kind,
                         const int32_t* q_len, const int32_t* ctx_len, const int32_t* bt_indptr,
                         const int32_t* bt_pages) {
-  if (Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0 || num_pages <= 0 || R < 0) return -2;
+  if (Hq <= 0 || Hkv <= 0 || D <= 0 || D % 16 != 0 || Hq % Hkv != 0 || num_pages <= 0 || R < 0) return -2;
   if (bt_indptr[0] != 0) return -5;
   for (int r = 0; r < R; ++r) {
     if (kind[r] != 0 && kind[r] != 1) return -3;
@@ -223,6 +228,7 @@ int hfx_oracle_gather_kv(int Hkv, int D, long num_pages, int R, const int32_t* c
                          const int32_t* bt_indptr, const int32_t* bt_pages, const uint16_t* pool,
                          int request, uint16_t* k_out, uint16_t* v_out) {
   if (request < 0 || request >= R) return -4;
+  if (D <= 0 || D % 16 != 0) return -2;
   orc_ctx c = {Hkv, Hkv, D, num_pages, bt_indptr, bt_pages, pool};
   long n = ctx_len[request];
   for (long t = 0; t < n; ++t) {
@@ -232,7 +238,7 @@ int hfx_oracle_gather_kv(int Hkv, int D, long num_pages, int R, const int32_t* c
     for (int g = 0; g < Hkv; ++g)
       for (int d = 0; d < D; ++d) {
         size_t o = ((size_t)t * Hkv + g) * D + d;
-        k_out[o] = pool[block_base(&c, page, g, 0) + (size_t)slot * D + d];
+        k_out[o] = pool[block_base(&c, page, g, 0) + k_offset(slot, d)];
         v_out[o] = pool[block_base(&c, page, g, 1) + (size_t)d * ORC_PAGE + slot];
       }
   }

@@ -4,12 +4,12 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 6u
+#define HFX_DESC_VERSION 7u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
-#define HFX_PLAN_WGS 256         /* planning width: 256 compute units x 1 resident workgroup */
+#define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
 #define HFX_KEY_TILE 64          /* keys per prefill tile (4 pages) */
-#define HFX_WAVE_ROWS 64         /* query rows one wavefront owns in a prefill item (two MFMA row blocks) */
+#define HFX_WAVE_ROWS 32         /* query rows one wavefront owns in a prefill item (one MFMA row block) */
 
 enum { HFX_ITEM_DECODE = 0, HFX_ITEM_PREFILL = 1 };
 
@@ -42,7 +42,7 @@ struct HfxReq {
 //  decode : h0 = first kv-head, hn = kv-heads covered (1, 2 or 4; one wavefront per head, the
 //           remaining wavefronts split the pages), kb/ke = request-relative page range.
 //  prefill: h0 = first q-head, hn = q-heads covered (1, 2 or 4), row0 = first chunk row,
-//           nrows = rows covered (64 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
+//           nrows = rows covered (32 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
 //  group >= 0: the item is one of several splits; its partial goes to workspace rows
 //           [slot_row, slot_row + rows) and the merge kernel combines the group afterwards.
 struct HfxItem {

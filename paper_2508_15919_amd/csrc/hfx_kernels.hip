@@ -20,7 +20,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define NEG_INF (-__builtin_inff())
 
 struct KArgs {
-  char* desc;            // device descriptor blob
+  const char* desc;      // device descriptor blob (read-only here; the control words go through `ctrl`)
   const __bf16* q;       // [T][Hq][D]
   const __bf16* pool;    // [pages][Hkv][2][16*D]
   float* ws;             // split partials
@@ -29,18 +29,20 @@ struct KArgs {
 
 template <int D>
 struct Smem {
-  // prefill: two K tiles (64 keys each), token-major rows padded by 16 B to spread the banks
-  static constexpr int kKStride = D * 2 + 16;
-  static constexpr int kKBytes = HFX_KEY_TILE * kKStride;
-  // decode: per-wavefront partial rows [4][16][D + 4] floats
+  // prefill: one K tile of 64 keys in operand order, [D/16][64 keys][16 dims]; two such buffers
+  static constexpr int kKBytes = HFX_KEY_TILE * D * 2;
+  // decode: per-wavefront partial rows [4][16][D + 4] floats (lives in the first K buffer + spill-over)
   static constexpr int kPartStride = D + 4;
   static constexpr int kPartBytes = 4 * 16 * kPartStride * 4;
-  static constexpr int kBytes = 2 * kKBytes > kPartBytes ? 2 * kKBytes : kPartBytes;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// Exchange between lane n and lane n ^ 32.
+__device__ __forceinline__ float max_xor32(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
+__device__ __forceinline__ float sum_xor32(float x) { return x + __shfl_xor(x, 32, 64); }
 
 // zero the elements e >= nv of an 8-element bf16 vector (nv may be <= 0 or >= 8)
 __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
@@ -69,7 +71,15 @@ struct MergeShape {
 };
 
 template <int D>
-__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(KArgs a) {
+__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __restrict__ desc,
+                                                               const float* __restrict__ ws,
+                                                               __bf16* __restrict__ out) {
+  KArgs a;
+  a.desc = desc;
+  a.q = nullptr;
+  a.pool = nullptr;
+  a.ws = const_cast<float*>(ws);
+  a.out = out;
   constexpr int C4 = MergeShape<D>::kCols, RB = MergeShape<D>::kRows, SL = kMergeSplitLanes;
   __shared__ float s_max[RB][SL];
   __shared__ float s_l[RB][SL];
@@ -167,9 +177,9 @@ __device__ __forceinline__ void decode_load(PairRegs<D>& r, const __bf16* pool, 
   const __bf16* kp = pool + (((long)(k_sel ? pg1 : pg0) * Hkv + g) * 2) * kBlock + k_off;
   const __bf16* vp = pool + (((long)(v_sel ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock + v_off;
 #pragma unroll
-  for (int kk = 0; kk < D / 32; ++kk) {
-    r.ka[kk] = ld16(kp + kk * 32);
-    r.kb[kk] = ld16(kp + 4 * D + kk * 32);
+  for (int kk = 0; kk < D / 32; ++kk) {   // 32 dimensions = two 16-dimension groups of 256 elements each
+    r.ka[kk] = ld16(kp + kk * 512);
+    r.kb[kk] = ld16(kp + kk * 512 + 4 * 16);
   }
 #pragma unroll
   for (int b = 0; b < D / 16; ++b) r.v[b] = ld16(vp + b * 256);
@@ -252,7 +262,7 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
   // K rows of the two score tiles: row rho of tile A is (page rho>>3, token ((rho>>2)&1)*8 + (rho&3)),
   // tile B the same + 4 tokens.  V: lane group j reads tokens (j&1)*8.. of page j>>1 for row d = 16b + n.
   const int k_sel = n >> 3;
-  const int k_off = (((n >> 2) & 1) * 8 + (n & 3)) * D + j * 8;
+  const int k_off = (j >> 1) * 256 + (((n >> 2) & 1) * 8 + (n & 3)) * 16 + (j & 1) * 8;
   const int v_sel = j >> 1;
   const int v_off = n * 16 + (j & 1) * 8;
   const int tok_lane = (j >> 1) * 16 + (j & 1) * 8;   // first of this lane's 8 tokens inside the pair
@@ -350,27 +360,21 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
 }
 
 // ----------------------------------------------------------------------------------------------
-// Prefill item.  Four wavefronts, each owning 64 chunk rows (two MFMA row blocks) of one
-// q-head; all four share the kv-head.  Operand traffic, not MFMA issue, is what bounds this
-// loop on CDNA4, so every operand fetched is used twice and the two contractions take their
-// tiles over two different paths:
-//   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows read from an LDS tile (staged once per
-//                                                 workgroup, double buffered), B = Q^T in registers;
-//   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows loaded straight from the page pool
-//                                                 (a dimension-major V block already has the MFMA
-//                                                 operand layout), B = P^T from the score registers.
-// Each lane owns one query row per row block (a column of S^T and O^T), so the running maximum,
-// sum and rescale are lane-local up to one exchange with lane ^ 32.  The K rows of a score tile
-// are taken in the order that leaves every lane with 8 consecutive keys of one page per 16-key
-// MFMA step.
+// Prefill item.  Four wavefronts, each owning 32 chunk rows of one q-head; all four share the
+// kv-head.  On CDNA4 this loop is bounded by operand delivery (an LDS read or a vector-memory
+// load of a 1 KB MFMA operand costs about 16 cycles of its unit per CU, an MFMA 32x32x16 takes
+// 32 cycles of one of four SIMDs), so the two contractions take their tiles over two paths:
+//   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows from an LDS tile that the workgroup fills
+//                                                 once per 64 keys with direct-to-LDS loads (double
+//                                                 buffered; the page's K block is already in operand
+//                                                 order), B = Q^T in registers;
+//   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows loaded straight from the page pool (a
+//                                                 dimension-major V block is the operand layout),
+//                                                 B = P^T from the score registers.
+// Each lane owns one query row (a column of S^T and O^T), so the running maximum, sum and rescale
+// are lane-local up to one exchange with lane ^ 32.  The K rows of a score tile are taken in the
+// order that leaves every lane with 8 consecutive keys of one page per 16-key MFMA step.
 // ----------------------------------------------------------------------------------------------
-template <int D>
-struct KStage {
-  static constexpr int kChunks = 4 * 2 * D;   // 16-byte chunks of K per 64-key tile
-  static constexpr int kPer = kChunks / HFX_WG_THREADS;
-  bf16x8 k[kPer];
-};
-
 struct TilePages {
   int pg[4];
 };
@@ -385,60 +389,90 @@ __device__ __forceinline__ TilePages tile_pages(const int* bt, int last_page, in
   return t;
 }
 
+// Asynchronous copy of one 64-key K tile into `kbuf`, laid out [D/16][64 keys][16 dims].  One
+// direct-to-LDS instruction moves 1 KB: the 32-byte pieces of 32 keys (two pages) for one
+// 16-dimension group; the (D/16)*2 instructions of a tile are dealt out over the four wavefronts.
 template <int D>
-__device__ __forceinline__ void k_stage_load(KStage<D>& r, const __bf16* pool, const TilePages& tp, int Hkv, int g,
-                                             int tid) {
-  constexpr int CH = 2 * D;   // 16-byte chunks per (page, head) K block
+__device__ __forceinline__ void k_tile_async(char* kbuf, const __bf16* pool, const TilePages& tp, int Hkv, int g,
+                                             int wave, int lane) {
+  constexpr int kPerWave = (D / 16) * 2 / 4;
   constexpr long kBlock = 16 * D;
 #pragma unroll
-  for (int i = 0; i < KStage<D>::kPer; ++i) {
-    const int c = i * HFX_WG_THREADS + tid;
-    const int pi = c / CH, w = c % CH;
-    const int pg = pi == 0 ? tp.pg[0] : pi == 1 ? tp.pg[1] : pi == 2 ? tp.pg[2] : tp.pg[3];
-    r.k[i] = ld16(pool + (((long)pg * Hkv + g) * 2) * kBlock + w * 8);
+  for (int i = 0; i < kPerWave; ++i) {
+    const int q = wave * kPerWave + i;
+    const int kk = q >> 1, kh = q & 1;
+    const int pg_lo = kh ? tp.pg[2] : tp.pg[0], pg_hi = kh ? tp.pg[3] : tp.pg[1];
+    const int pg = (lane >> 5) ? pg_hi : pg_lo;
+    const __bf16* src = pool + (((long)pg * Hkv + g) * 2) * kBlock + (kk * 16 + ((lane >> 1) & 15)) * 16 + (lane & 1) * 8;
+    char* dst = kbuf + kk * (HFX_KEY_TILE * 32) + kh * 1024;
+    // Issued as inline assembly on purpose: the compiler's wait-count pass treats its own
+    // direct-to-LDS intrinsic as aliasing every later LDS read and drains the whole vector-memory
+    // queue in front of them, which would stall the V stream on every tile.  Here the copy is
+    // ordered by hand: the caller waits for vmcnt(0) and crosses a barrier before the tile is read.
+    const unsigned lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds)
+                 : "m0", "memory");
   }
 }
 
 template <int D>
-__device__ __forceinline__ void k_stage_store(const KStage<D>& r, char* kbuf, int tid) {
-  constexpr int CH = 2 * D;
-  constexpr int KS = Smem<D>::kKStride;
+struct VHalf {
+  bf16x8 f[2][D / 32];     // V^T operand fragments of 32 keys: [page][32-dimension block]
+  static constexpr int kLoads = 2 * (D / 32);
+};
+
+// vh.f[sp][b] = V^T rows 32b+n, keys 8j.. of page pg_sp, loaded straight from the pool
+template <int D>
+__device__ __forceinline__ void v_half_load(VHalf<D>& vh, const __bf16* pool, int pg0, int pg1, int Hkv, int g,
+                                            int v_lane) {
+  constexpr long kBlock = 16 * D;
 #pragma unroll
-  for (int i = 0; i < KStage<D>::kPer; ++i) {
-    const int c = i * HFX_WG_THREADS + tid;
-    const int pi = c / CH, w = c % CH;
-    const int tok = w / (D / 8), col = w % (D / 8);   // K chunk w: token, 16-byte column
-    *reinterpret_cast<bf16x8*>(kbuf + (pi * 16 + tok) * KS + col * 16) = r.k[i];
+  for (int sp = 0; sp < 2; ++sp) {
+    const __bf16* vb = pool + (((long)(sp ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock + v_lane;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) vh.f[sp][b] = ld16(vb + b * 512);
   }
 }
 
-// Softmax of one row block's 32 scores (one MFMA result tile).  `m` is the reference exponent
-// (base-2 domain) of the running sums; it is only raised -- and O, l rescaled -- when some row's
-// maximum has grown by more than 2^8 over it, which keeps every weight below 2^8 and makes the
-// rescale rare.  s[v] is key key0 + (v>>3)*16 + (v&7)   (key0 already holds the lane's 8j).
-template <int D, bool MASK>
-__device__ __forceinline__ void softmax_block(f32x16& s, f32x16* o, float& m, float& l, bf16x8* pb, float sl2,
-                                              int key0, int pos) {
-  if (MASK) {
+// Per-wavefront state of a prefill item that lives across key tiles.
+template <int D>
+struct PrefillWave {
+  f32x16 o[D / 32];        // O^T accumulators per 32-dimension block
+  bf16x8 qf[D / 16];       // Q^T operand fragments
+  float m, l;              // reference exponent (base-2 domain) and running sum
+  int pos;                 // last key this lane's row may see
+};
+
+// Softmax of 32 scores (one MFMA result tile) of this lane's row.  `m` is the reference exponent
+// of the running sums; it is only raised -- and O, l rescaled -- when some row's maximum has
+// grown by more than 2^8 over it, which keeps every weight below 2^8 and makes the rescale rare.
+// s[v] is key key0 + (v>>3)*16 + (v&7)   (key0 already includes the lane's 8j).
+template <int D>
+__device__ __forceinline__ void softmax_block(f32x16& s, PrefillWave<D>& w, bf16x8* pb, float sl2, bool masked,
+                                              int key0) {
+  if (masked) {                // wave-uniform; the empty asm keeps the compiler from turning the rare
+    asm volatile("" ::: );     // masking into selects executed on every tile
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int key = key0 + (v >> 3) * 16 + (v & 7);
-      s[v] = key <= pos ? s[v] : NEG_INF;
+      s[v] = key <= w.pos ? s[v] : NEG_INF;
     }
   }
   float mx = fmaxf(s[0], s[1]);
 #pragma unroll
   for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(s[v], s[v + 1]));
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;
-  if (__any(mx > m + 8.0f)) {
-    const float mn = fmaxf(m, mx);
-    const float alpha = fast_exp2(m - (mn == NEG_INF ? 0.f : mn));
-    l *= alpha;
+  mx = max_xor32(mx) * sl2;
+  if (__any(mx > w.m + 8.0f)) {
+    const float mn = fmaxf(w.m, mx);
+    const float alpha = fast_exp2(w.m - (mn == NEG_INF ? 0.f : mn));
+    w.l *= alpha;
 #pragma unroll
-    for (int b = 0; b < D / 32; ++b) o[b] *= alpha;
-    m = mn;
+    for (int b = 0; b < D / 32; ++b) w.o[b] *= alpha;
+    w.m = mn;
   }
-  const float mneg = m == NEG_INF ? 0.f : -m;
+  const float mneg = w.m == NEG_INF ? 0.f : -w.m;
   float ps = 0.f;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
@@ -446,91 +480,92 @@ __device__ __forceinline__ void softmax_block(f32x16& s, f32x16* o, float& m, fl
     ps += pv;
     pb[v >> 3][v & 7] = (__bf16)pv;
   }
-  l += ps;
+  w.l += ps;
 }
 
-// Per-wavefront state of a prefill item that lives across key tiles.
 template <int D>
-struct PrefillWave {
-  f32x16 o[2][D / 32];     // O^T accumulators, [row block][32-dimension block]
-  bf16x8 qf[2][D / 16];    // Q^T operand fragments
-  float m[2], l[2];        // reference exponent and running sum per row block
-  int pos[2];              // last key each of this lane's two rows may see
+struct KFrags {
+  bf16x8 f[D / 16];        // K operand fragments of 32 keys, one per 16-dimension group
 };
 
-// One 64-key tile: issue the next tile's K loads, run the two 32-key halves from the current LDS
-// buffer, then publish the next K tile into the other buffer.  MASK selects the variant that
-// applies the causal / context-end masks (tiles that reach past some row's horizon).
-template <int D, bool MASK>
-__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, KStage<D>& st, TilePages& tp, const __bf16* pool,
-                                             const int* bt, int last_page, char* smem, int& buf, int kt, int ke,
-                                             int wave_kend, int ctx_len, int Hkv, int g, int k_lane, int v_lane,
-                                             int j, float sl2, int tid) {
-  constexpr int KS = Smem<D>::kKStride;
-  constexpr long kBlock = 16 * D;
-  const bool more = kt + HFX_KEY_TILE < ke;
-  const TilePages cur = tp;
-  if (more) {
-    tp = tile_pages(bt, last_page, kt + HFX_KEY_TILE);
-    k_stage_load<D>(st, pool, tp, Hkv, g, tid);
-  }
-  if (kt < wave_kend) {
-    const char* kb = smem + buf * Smem<D>::kKBytes + k_lane;
+// kb points at this lane's K row of a 32-key half inside the LDS tile
+template <int D>
+__device__ __forceinline__ void k_frags_read(KFrags<D>& kf, const char* kb) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      // V^T fragments of this half, straight from the pool: vf[sp][b] = rows 32b+n, keys 8j.. of page 2u+sp
-      bf16x8 vf[2][D / 32];
+  for (int kk = 0; kk < D / 16; ++kk)
+    kf.f[kk] = *reinterpret_cast<const bf16x8*>(kb + kk * (HFX_KEY_TILE * 32));
+}
+
+// 32 keys (two pages) against the wavefront's 32 rows; key0 is the first key of the half.
+template <int D>
+__device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, const KFrags<D>& kf, bool masked,
+                                             bool past_ctx, int key0, int ctx_len, int j, float sl2) {
+  f32x16 s;
 #pragma unroll
-      for (int sp = 0; sp < 2; ++sp) {
-        const __bf16* vb = pool + (((long)cur.pg[2 * u + sp] * Hkv + g) * 2 + 1) * kBlock + v_lane;
+  for (int kk = 0; kk < D / 16; ++kk) {
+    if (kk == 0) {
+      f32x16 z;
 #pragma unroll
-        for (int b = 0; b < D / 32; ++b) vf[sp][b] = ld16(vb + b * 512);
-      }
-      f32x16 s[2];
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kb + u * 32 * KS + kk * 32);
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          if (kk == 0) {
-            f32x16 z;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) z[v] = 0.f;
-            s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[rb][kk], z, 0, 0, 0);
-          } else {
-            s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[rb][kk], s[rb], 0, 0, 0);
-          }
-        }
-      }
-      if (MASK) {   // a tile that runs past the context: unused V slots may hold anything
-        if (kt + HFX_KEY_TILE > ctx_len) {
-#pragma unroll
-          for (int sp = 0; sp < 2; ++sp)
-#pragma unroll
-            for (int b = 0; b < D / 32; ++b)
-              vf[sp][b] = keep_first(vf[sp][b], ctx_len - (kt + (2 * u + sp) * 16 + j * 8));
-        }
-      }
-      bf16x8 pb[2][2];
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-        softmax_block<D, MASK>(s[rb], w.o[rb], w.m[rb], w.l[rb], pb[rb], sl2, kt + u * 32 + j * 8, w.pos[rb]);
-#pragma unroll
-      for (int sp = 0; sp < 2; ++sp)
-#pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-          for (int rb = 0; rb < 2; ++rb)
-            w.o[rb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[sp][b], pb[rb][sp], w.o[rb][b], 0, 0, 0);
+      for (int v = 0; v < 16; ++v) z[v] = 0.f;
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.f[kk], w.qf[kk], z, 0, 0, 0);
+    } else {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.f[kk], w.qf[kk], s, 0, 0, 0);
     }
   }
-  if (more) k_stage_store<D>(st, smem + (buf ^ 1) * Smem<D>::kKBytes, tid);
-  __syncthreads();
-  buf ^= 1;
+  if (past_ctx) {              // the half runs past the context: unused V slots may hold anything
+    asm volatile("" ::: );
+#pragma unroll
+    for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+      for (int b = 0; b < D / 32; ++b) vh.f[sp][b] = keep_first(vh.f[sp][b], ctx_len - (key0 + sp * 16 + j * 8));
+  }
+  bf16x8 pb[2];
+  softmax_block<D>(s, w, pb, sl2, masked, key0 + j * 8);
+#pragma unroll
+  for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+      w.o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh.f[sp][b], pb[sp], w.o[b], 0, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
+#define HFX_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// One 64-key tile from the LDS buffer `kcur`.  Order of the memory traffic: the V fragments of
+// the second half are requested first; the copy of the next K tile into `knext` and the V
+// fragments of the next tile's first half are requested once the last K operands of this tile
+// have been read out of LDS, so that they have the whole second half to arrive.
+template <int D>
+__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, VHalf<D>& vx, VHalf<D>& vy,
+                                             const char* kcur, char* knext, const __bf16* pool, const int* bt,
+                                             int last_page, int kt, int ke, int wave_kend, int wave_pmin,
+                                             int ctx_len, int Hkv, int g, int k_lane, int v_lane, int j, float sl2,
+                                             int wave, int lane) {
+  const bool active = kt < wave_kend;
+  const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
+  const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
+  // Every load below is issued unconditionally (past the end of the range the page indices are
+  // clamped, so the addresses stay valid and the data is simply not used): the wait counters the
+  // compiler derives are compile-time constants, and a path that skipped a load would force
+  // them to zero and stall the pipeline on every tile.
+  KFrags<D> kf;
+  v_half_load<D>(vy, pool, tp.pg[2], tp.pg[3], Hkv, g, v_lane);
+  k_frags_read<D>(kf, kcur + k_lane);
+  if (active) prefill_half<D>(w, vx, kf, masked, past_ctx, kt, ctx_len, j, sl2);
+  k_frags_read<D>(kf, kcur + 1024 + k_lane);
+  tp = tile_pages(bt, last_page, kt + HFX_KEY_TILE);
+  k_tile_async<D>(knext, pool, tp, Hkv, g, wave, lane);
+  v_half_load<D>(vx, pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
+  if (active) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
+  // the next K tile must have landed before anyone reads it
+  HFX_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copy waited for above
+  asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
 }
 
 template <int D>
-__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
+__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* kbuf0,
+                             char* kbuf1) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -544,83 +579,76 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
   const int wave_kend = r0 < rq.q_len ? p + min(r0 + HFX_WAVE_ROWS, rq.q_len) : 0;   // keys >= this: nothing to do
   const int wave_pmin = p + r0;                                 // keys <= this are visible to every row
   const float sl2 = H->softmax_scale * 1.4426950408889634f;
+  const int qrow = r0 + n;
+  const int qc = qrow < rq.q_len ? qrow : rq.q_len - 1;
 
   PrefillWave<D> w;
-  int qrow[2];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    qrow[rb] = r0 + rb * 32 + n;
-    const int qc = qrow[rb] < rq.q_len ? qrow[rb] : rq.q_len - 1;
-    w.pos[rb] = p + qc;
+  w.pos = p + qc;
+  {
     const __bf16* qp = a.q + (((long)rq.q_start + qc) * Hq + head) * D + j * 8;
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) w.qf[rb][kk] = ld16(qp + kk * 16);
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) w.o[rb][b][v] = 0.f;
-    w.m[rb] = NEG_INF;
-    w.l[rb] = 0.f;
+    for (int kk = 0; kk < D / 16; ++kk) w.qf[kk] = ld16(qp + kk * 16);
   }
+#pragma unroll
+  for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w.o[b][v] = 0.f;
+  w.m = NEG_INF;
+  w.l = 0.f;
 
   const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
   const int last_page = rq.n_pages - 1;
-  // LDS row of this lane's K row in score sub-tile 0 (sub-tile u adds 32 rows)
+  // row of this lane's key inside a 32-key half of the LDS tile (32 bytes per key and 16-dimension group)
   const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
-  const int k_lane = krow * Smem<D>::kKStride + j * 16;
+  const int k_lane = krow * 32 + j * 16;
   const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
 
-  KStage<D> st;
   TilePages tp = tile_pages(bt, last_page, it.kb);
-  k_stage_load<D>(st, a.pool, tp, Hkv, g, tid);
-  k_stage_store<D>(st, smem, tid);
-  __syncthreads();
-  int buf = 0;
-  // tiles whose every key every row of this wavefront sees come first and need no masks
-  int kt_mask = ((max(wave_pmin - (HFX_KEY_TILE - 2), 0) + HFX_KEY_TILE - 1) / HFX_KEY_TILE) * HFX_KEY_TILE;
-  kt_mask = min(max(kt_mask, it.kb), it.ke);
-  int kt = it.kb;
-  for (; kt < kt_mask; kt += HFX_KEY_TILE)
-    prefill_tile<D, false>(w, st, tp, a.pool, bt, last_page, smem, buf, kt, it.ke, wave_kend, rq.ctx_len, Hkv, g,
-                           k_lane, v_lane, j, sl2, tid);
-  for (; kt < it.ke; kt += HFX_KEY_TILE)
-    prefill_tile<D, true>(w, st, tp, a.pool, bt, last_page, smem, buf, kt, it.ke, wave_kend, rq.ctx_len, Hkv, g,
-                          k_lane, v_lane, j, sl2, tid);
+  k_tile_async<D>(kbuf0, a.pool, tp, Hkv, g, wave, lane);
+  VHalf<D> vx, vy;
+  v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
+  HFX_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  for (int kt = it.kb; kt < it.ke; kt += 2 * HFX_KEY_TILE) {
+    prefill_tile<D>(w, tp, vx, vy, kbuf0, kbuf1, a.pool, bt, last_page, kt, it.ke, wave_kend, wave_pmin,
+                    rq.ctx_len, Hkv, g, k_lane, v_lane, j, sl2, wave, lane);
+    if (kt + HFX_KEY_TILE < it.ke)
+      prefill_tile<D>(w, tp, vx, vy, kbuf1, kbuf0, a.pool, bt, last_page, kt + HFX_KEY_TILE, it.ke, wave_kend,
+                      wave_pmin, rq.ctx_len, Hkv, g, k_lane, v_lane, j, sl2, wave, lane);
+  }
 
-  // o[rb][b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row qrow[rb]
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const float lsum = w.l[rb] + __shfl_xor(w.l[rb], 32, 64);
-    if (it.group < 0) {
-      if (qrow[rb] < rq.q_len) {
-        const float inv = 1.0f / lsum;
-        __bf16* dst = a.out + (((long)rq.q_start + qrow[rb]) * Hq + head) * D + 4 * j;
-#pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 ob;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(w.o[rb][b][q4 * 4 + e] * inv);
-            *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
-          }
-      }
-    } else {
-      float* ws_acc = a.ws;
-      float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
-      const long pr = (long)it.slot_row + wave * HFX_WAVE_ROWS + rb * 32 + n;
-      float* dst = ws_acc + pr * D + 4 * j;
+  // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
+  const float lsum = sum_xor32(w.l);
+  if (it.group < 0) {
+    if (qrow < rq.q_len) {
+      const float inv = 1.0f / lsum;
+      __bf16* dst = a.out + (((long)rq.q_start + qrow) * Hq + head) * D + 4 * j;
 #pragma unroll
       for (int b = 0; b < D / 32; ++b)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 t = {w.o[rb][b][q4 * 4], w.o[rb][b][q4 * 4 + 1], w.o[rb][b][q4 * 4 + 2], w.o[rb][b][q4 * 4 + 3]};
-          *reinterpret_cast<f32x4*>(dst + b * 32 + q4 * 8) = t;
+          bf16x4 ob;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(w.o[b][q4 * 4 + e] * inv);
+          *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
         }
-      if (j == 0) {
-        ws_ml[pr * 2] = w.m[rb];
-        ws_ml[pr * 2 + 1] = lsum;
+    }
+  } else {
+    float* ws_acc = a.ws;
+    float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
+    const long pr = (long)it.slot_row + wave * HFX_WAVE_ROWS + n;
+    float* dst = ws_acc + pr * D + 4 * j;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 t = {w.o[b][q4 * 4], w.o[b][q4 * 4 + 1], w.o[b][q4 * 4 + 2], w.o[b][q4 * 4 + 3]};
+        *reinterpret_cast<f32x4*>(dst + b * 32 + q4 * 8) = t;
       }
+    if (j == 0) {
+      ws_ml[pr * 2] = w.m;
+      ws_ml[pr * 2 + 1] = lsum;
     }
   }
 }
@@ -632,11 +660,22 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
 // workgroup to leave restores it to zero so the descriptor can serve the next launch.
 // ----------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(HFX_WG_THREADS, 1) void mixed_attention_kernel(KArgs a) {
-  __shared__ __attribute__((aligned(16))) char smem[Smem<D>::kBytes];
+__global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
+    const char* __restrict__ desc, int* __restrict__ ctrl, const __bf16* __restrict__ q,
+    const __bf16* __restrict__ pool, float* __restrict__ ws, __bf16* __restrict__ out) {
+  // the descriptor tables are read-only and distinct from everything written here, which lets
+  // the compiler fetch them with scalar loads that do not queue behind the KV stream
+  KArgs a;
+  a.desc = desc;
+  a.q = q;
+  a.pool = pool;
+  a.ws = ws;
+  a.out = out;
+  __shared__ __attribute__((aligned(1024))) char kbuf0[Smem<D>::kKBytes];
+  __shared__ __attribute__((aligned(1024))) char kbuf1[Smem<D>::kKBytes];
+  __shared__ __attribute__((aligned(16))) char part[Smem<D>::kPartBytes];
   __shared__ int s_next;
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
-  int* ctrl = reinterpret_cast<int*>(a.desc + H->off_ctrl);
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const HfxReq* reqs = reinterpret_cast<const HfxReq*>(a.desc + H->off_req);
   const int n_items = H->n_items;
@@ -650,8 +689,8 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 1) void mixed_attention_kernel(KArg
     if (threadIdx.x == 0) nxt = atomicAdd(&ctrl[0], 1);
     const HfxItem it = items[idx];
     const HfxReq rq = reqs[it.req];
-    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem);
-    else prefill_item<D>(a, H, it, rq, smem);
+    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, part);
+    else prefill_item<D>(a, H, it, rq, kbuf0, kbuf1);
     if (threadIdx.x == 0) s_next = nxt;
     __syncthreads();
   }
@@ -680,7 +719,7 @@ __global__ void gather_kv_kernel(const char* desc, const uint16_t* pool, int req
     const long pg = bt[t / HFX_PAGE];
     const int slot = (int)(t % HFX_PAGE);
     const long blk = ((pg * Hkv + g) * 2) * (16L * D);
-    k_out[i] = pool[blk + (long)slot * D + d];
+    k_out[i] = pool[blk + ((long)(d / 16) * HFX_PAGE + slot) * 16 + d % 16];
     v_out[i] = pool[blk + 16L * D + (long)d * HFX_PAGE + slot];
   }
 }
@@ -692,25 +731,26 @@ hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
 }
 
-hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, int max_group_rows, void* desc,
-                                  const void* q, const void* pool, void* ws, void* out, hipStream_t stream) {
-  KArgs a;
-  a.desc = static_cast<char*>(desc);
-  a.q = static_cast<const __bf16*>(q);
-  a.pool = static_cast<const __bf16*>(pool);
-  a.ws = static_cast<float*>(ws);
-  a.out = static_cast<__bf16*>(out);
+hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, int max_group_rows, unsigned off_ctrl,
+                                  void* desc, const void* q, const void* pool, void* ws, void* out,
+                                  hipStream_t stream) {
+  const char* d = static_cast<const char*>(desc);
+  int* ctrl = reinterpret_cast<int*>(static_cast<char*>(desc) + off_ctrl);
+  const __bf16* qp = static_cast<const __bf16*>(q);
+  const __bf16* pp = static_cast<const __bf16*>(pool);
+  float* wp = static_cast<float*>(ws);
+  __bf16* op = static_cast<__bf16*>(out);
   if (head_dim == 128)
-    hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
+    hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
   else
-    hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, a);
+    hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
   if (n_groups > 0) {
     if (head_dim == 128) {
       const int chunks = (max_group_rows + MergeShape<128>::kRows - 1) / MergeShape<128>::kRows;
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, a);
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
     } else {
       const int chunks = (max_group_rows + MergeShape<64>::kRows - 1) / MergeShape<64>::kRows;
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, a);
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
     }
   }
   return hipGetLastError();

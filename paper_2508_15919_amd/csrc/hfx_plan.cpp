@@ -20,7 +20,7 @@ static const int kMinDecodeTokens = 128;
 static const int kMinPrefillKeys = 256;
 static const int kMaxSplits = 64;
 static const int kDecodeItemsPerWg = 8;    // decode partials are small (rows of D + 2 floats per q-head)
-static const int kPrefillItemsPerWg = 2;   // prefill partials are 256 rows: split only where balance needs it
+static const int kPrefillItemsPerWg = 2;   // prefill partials are 128 rows: split only where balance needs it
 
 static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
 static int q_heads_per_item(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1); }

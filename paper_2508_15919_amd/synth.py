@@ -12,8 +12,9 @@ Table 1).  No dataset item is reproduced: attention cost depends on lengths
 only, so lengths are drawn from distributions and all values are N(0,1).
 
 Pool layout written here (bf16 bits, uint16): pool[page][kv_head][0] holds the
-keys token-major (slot*D + d), pool[page][kv_head][1] holds the values
-dimension-major (d*16 + slot).
+keys blocked by 16 dimensions, viewed as [D/16][16 slots][16] (element (slot, d)
+at ((d//16)*16 + slot)*16 + d%16); pool[page][kv_head][1] holds the values
+dimension-major, viewed as [D][16 slots].
 """
 from __future__ import annotations
 
@@ -181,9 +182,9 @@ def poison_tails(batch: StepBatch) -> None:
             reach[int(p)] = max(reach.get(int(p), 0), used)
     for p, used in reach.items():
         if used < PAGE:
-            k = batch.pool[p, :, 0].reshape(batch.num_kv_heads, PAGE, d)
+            k = batch.pool[p, :, 0].reshape(batch.num_kv_heads, d // 16, PAGE, 16)
             v = batch.pool[p, :, 1].reshape(batch.num_kv_heads, d, PAGE)
-            k[:, used:, :] = BF16_NAN
+            k[:, :, used:, :] = BF16_NAN
             v[:, :, used:] = BF16_NAN
 
 

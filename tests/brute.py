@@ -10,9 +10,9 @@ def unpage(b, r):
     c = int(b.ctx_len[r])
     D = b.head_dim
     pages = b.bt_pages[b.bt_indptr[r]: b.bt_indptr[r] + (c + 15) // 16]
-    k_pages = b.pool[pages, :, 0].reshape(len(pages), b.num_kv_heads, 16, D)      # [pg, g, slot, d]
+    k_pages = b.pool[pages, :, 0].reshape(len(pages), b.num_kv_heads, D // 16, 16, 16)   # [pg, g, d/16, slot, d%16]
     v_pages = b.pool[pages, :, 1].reshape(len(pages), b.num_kv_heads, D, 16)      # [pg, g, d, slot]
-    k = k_pages.transpose(0, 2, 1, 3).reshape(len(pages) * 16, b.num_kv_heads, D)[:c]
+    k = k_pages.transpose(0, 3, 1, 2, 4).reshape(len(pages) * 16, b.num_kv_heads, D)[:c]
     v = v_pages.transpose(0, 3, 1, 2).reshape(len(pages) * 16, b.num_kv_heads, D)[:c]
     return bf16_bits_to_f64(k), bf16_bits_to_f64(v)
 

@@ -33,7 +33,7 @@ def manual_batch(Hq, Hkv, D, kind, q_len, ctx_len, q_f32, k_f32, v_f32, pages=No
         for t in range(ctx_len[r]):
             pg = pages[indptr[r] + t // 16]
             for g in range(Hkv):
-                pool[pg, g, 0].reshape(16, D)[t % 16] = kb[t, g]
+                pool[pg, g, 0].reshape(D // 16, 16, 16)[:, t % 16, :] = kb[t, g].reshape(D // 16, 16)
                 pool[pg, g, 1].reshape(D, 16)[:, t % 16] = vb[t, g]
     q = f32_to_bf16_bits(np.concatenate(q_f32, axis=0))
     return StepBatch(Hq, Hkv, D, total + 2, np.array(kind, np.int32), np.array(q_len, np.int32),
@@ -41,7 +41,7 @@ def manual_batch(Hq, Hkv, D, kind, q_len, ctx_len, q_f32, k_f32, v_f32, pages=No
 
 
 def test_brute_force_on_unpaged_kv(oracle):
-    for seed, (Hq, Hkv, D) in enumerate([(4, 2, 64), (8, 1, 128), (6, 6, 32), (32, 8, 128)]):
+    for seed, (Hq, Hkv, D) in enumerate([(4, 2, 64), (8, 1, 128), (6, 6, 32), (32, 8, 128), (3, 1, 16)]):
         b = small_mixed(seed, Hq, Hkv, D)
         got = oracle.attention_batch(b)
         ref = brute.dense_attention(b)
@@ -80,13 +80,16 @@ def test_golden_two_key_logistic(oracle):
             if line.startswith("out"):
                 k, v = line.split()
                 want[k] = float(v)
-    D = 2
-    q = [np.array([[[1.0, 0.0]]], np.float32)]
-    k = [np.array([[[0.0, 0.0]], [[1.0, 0.0]]], np.float32)]
-    v = [np.array([[[1.0, 0.0]], [[0.0, 1.0]]], np.float32)]
+    D = 16                       # the two coordinates of the example, zero padded to one 16-dimension block
+    e0, e1 = np.zeros(D, np.float32), np.zeros(D, np.float32)
+    e0[0], e1[1] = 1.0, 1.0
+    q = [e0.reshape(1, 1, D)]
+    k = [np.stack([np.zeros(D, np.float32), e0]).reshape(2, 1, D)]
+    v = [np.stack([e0, e1]).reshape(2, 1, D)]
     b = manual_batch(1, 1, D, [DECODE], [1], [2], q, k, v)
     got = oracle.attention_batch(b, scale=1.0)
     assert abs(got[0, 0, 0] - want["out0"]) < 1e-15 and abs(got[0, 0, 1] - want["out1"]) < 1e-15
+    assert np.all(got[0, 0, 2:] == 0.0)
     assert abs(want["out1"] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
 
 
