@@ -29,11 +29,13 @@ struct KArgs {
 
 template <int D>
 struct Smem {
-  // prefill: one K tile of 64 keys in operand order, [D/16][64 keys][16 dims]; two such buffers
+  // prefill: K tiles of 64 keys in operand order ([D/16][2][2][32 keys][8 dims]); three of them rotate
   static constexpr int kKBytes = HFX_KEY_TILE * D * 2;
-  // decode: per-wavefront partial rows [4][16][D + 4] floats (lives in the first K buffer + spill-over)
+  static constexpr int kKBuffers = 3;
+  // decode: per-wavefront partial rows [4][16][D + 4] floats (same memory; an item is one or the other)
   static constexpr int kPartStride = D + 4;
   static constexpr int kPartBytes = 4 * 16 * kPartStride * 4;
+  static constexpr int kBytes = kKBuffers * kKBytes > kPartBytes ? kKBuffers * kKBytes : kPartBytes;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -389,9 +391,9 @@ __device__ __forceinline__ TilePages tile_pages(const int* bt, int last_page, in
   return t;
 }
 
-// Asynchronous copy of one 64-key K tile into `kbuf`, laid out [D/16][64 keys][16 dims].  One
-// direct-to-LDS instruction moves 1 KB: the 32-byte pieces of 32 keys (two pages) for one
-// 16-dimension group; the (D/16)*2 instructions of a tile are dealt out over the four wavefronts.
+// Asynchronous copy of one 64-key K tile into `kbuf`, laid out [D/16][2 key halves][2 dimension
+// halves][32 keys][8 dims].  One direct-to-LDS instruction moves 1 KB: the 32-byte pieces of 32
+// keys (two pages) for one 16-dimension group; the (D/16)*2 instructions of a tile are dealt out over the four wavefronts.
 template <int D>
 __device__ __forceinline__ void k_tile_async(char* kbuf, const __bf16* pool, const TilePages& tp, int Hkv, int g,
                                              int wave, int lane) {
@@ -402,8 +404,10 @@ __device__ __forceinline__ void k_tile_async(char* kbuf, const __bf16* pool, con
     const int q = wave * kPerWave + i;
     const int kk = q >> 1, kh = q & 1;
     const int pg_lo = kh ? tp.pg[2] : tp.pg[0], pg_hi = kh ? tp.pg[3] : tp.pg[1];
-    const int pg = (lane >> 5) ? pg_hi : pg_lo;
-    const __bf16* src = pool + (((long)pg * Hkv + g) * 2) * kBlock + (kk * 16 + ((lane >> 1) & 15)) * 16 + (lane & 1) * 8;
+    // lane l fills LDS slot l of the 1 KB block: slot = 32 * (dimension half) + key, so that the 16
+    // lanes the LDS serves together later read 16 different bank groups
+    const int pg = ((lane >> 4) & 1) ? pg_hi : pg_lo;
+    const __bf16* src = pool + (((long)pg * Hkv + g) * 2) * kBlock + (kk * 16 + (lane & 15)) * 16 + (lane >> 5) * 8;
     char* dst = kbuf + kk * (HFX_KEY_TILE * 32) + kh * 1024;
     // Issued as inline assembly on purpose: the compiler's wait-count pass treats its own
     // direct-to-LDS intrinsic as aliasing every later LDS read and drains the whole vector-memory
@@ -494,6 +498,9 @@ __device__ __forceinline__ void k_frags_read(KFrags<D>& kf, const char* kb) {
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk)
     kf.f[kk] = *reinterpret_cast<const bf16x8*>(kb + kk * (HFX_KEY_TILE * 32));
+  // keep all the reads in front of the MFMA chain that consumes them: left alone, the scheduler
+  // sinks each read next to its MFMA to save registers and exposes the LDS latency eight times
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // 32 keys (two pages) against the wavefront's 32 rows; key0 is the first key of the half.
@@ -532,15 +539,18 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
 #define HFX_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // One 64-key tile from the LDS buffer `kcur`.  Order of the memory traffic: the V fragments of
-// the second half are requested first; the copy of the next K tile into `knext` and the V
-// fragments of the next tile's first half are requested once the last K operands of this tile
-// have been read out of LDS, so that they have the whole second half to arrive.
+// the second half are requested first; once the last K operands of this tile have been read out
+// of LDS, the V fragments of the next tile's first half are requested and the copy of the K tile
+// two tiles ahead goes into `kfill` (three buffers rotate, so the buffer being filled was last
+// read one tile ago and every wavefront has passed a barrier since).  Loads return in order: by the
+// time this tile's second-half V fragments have arrived, the K tile requested one tile earlier
+// has landed too, so the barrier at the end needs no wait of its own.
 template <int D>
 __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, VHalf<D>& vx, VHalf<D>& vy,
-                                             const char* kcur, char* knext, const __bf16* pool, const int* bt,
-                                             int last_page, int kt, int ke, int wave_kend, int wave_pmin,
-                                             int ctx_len, int Hkv, int g, int k_lane, int v_lane, int j, float sl2,
-                                             int wave, int lane) {
+                                             const char* kcur, char* kfill, const __bf16* pool, const int* bt,
+                                             int last_page, int kt, int wave_kend, int wave_pmin, int ctx_len,
+                                             int Hkv, int g, int k_lane, int v_lane, int j, float sl2, int wave,
+                                             int lane) {
   const bool active = kt < wave_kend;
   const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
   const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
@@ -554,18 +564,19 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
   if (active) prefill_half<D>(w, vx, kf, masked, past_ctx, kt, ctx_len, j, sl2);
   k_frags_read<D>(kf, kcur + 1024 + k_lane);
   tp = tile_pages(bt, last_page, kt + HFX_KEY_TILE);
-  k_tile_async<D>(knext, pool, tp, Hkv, g, wave, lane);
   v_half_load<D>(vx, pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
+  // The copy goes last: the compiler does not count it, so the waits it derives for the V
+  // fragments above would otherwise also wait for a copy issued in front of them.
+  const TilePages ahead = tile_pages(bt, last_page, kt + 2 * HFX_KEY_TILE);
+  k_tile_async<D>(kfill, pool, ahead, Hkv, g, wave, lane);
   if (active) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
-  // the next K tile must have landed before anyone reads it
-  HFX_WAIT_VMCNT(0);
-  __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copy waited for above
+  else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
+  __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
   asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
 }
 
 template <int D>
-__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* kbuf0,
-                             char* kbuf1) {
+__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -598,25 +609,32 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
 
   const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
   const int last_page = rq.n_pages - 1;
-  // row of this lane's key inside a 32-key half of the LDS tile (32 bytes per key and 16-dimension group)
+  // row of this lane's key inside a 32-key half of the LDS tile
   const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
-  const int k_lane = krow * 32 + j * 16;
+  const int k_lane = (j * 32 + krow) * 16;
   const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
 
   TilePages tp = tile_pages(bt, last_page, it.kb);
-  k_tile_async<D>(kbuf0, a.pool, tp, Hkv, g, wave, lane);
+  k_tile_async<D>(smem, a.pool, tp, Hkv, g, wave, lane);
+  {
+    const TilePages t1 = tile_pages(bt, last_page, it.kb + HFX_KEY_TILE);
+    k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, t1, Hkv, g, wave, lane);
+  }
   VHalf<D> vx, vy;
   v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
   HFX_WAIT_VMCNT(0);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  for (int kt = it.kb; kt < it.ke; kt += 2 * HFX_KEY_TILE) {
-    prefill_tile<D>(w, tp, vx, vy, kbuf0, kbuf1, a.pool, bt, last_page, kt, it.ke, wave_kend, wave_pmin,
+  int cur = 0;   // byte offset of the K buffer holding tile kt; the one two ahead is refilled
+  for (int kt = it.kb; kt < it.ke; kt += HFX_KEY_TILE) {
+    int fill = cur + 2 * Smem<D>::kKBytes;
+    if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
+    prefill_tile<D>(w, tp, vx, vy, smem + cur, smem + fill, a.pool, bt, last_page, kt, wave_kend, wave_pmin,
                     rq.ctx_len, Hkv, g, k_lane, v_lane, j, sl2, wave, lane);
-    if (kt + HFX_KEY_TILE < it.ke)
-      prefill_tile<D>(w, tp, vx, vy, kbuf1, kbuf0, a.pool, bt, last_page, kt + HFX_KEY_TILE, it.ke, wave_kend,
-                      wave_pmin, rq.ctx_len, Hkv, g, k_lane, v_lane, j, sl2, wave, lane);
+    cur += Smem<D>::kKBytes;
+    if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
   }
+  HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the range
 
   // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
   const float lsum = sum_xor32(w.l);
@@ -671,9 +689,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   a.pool = pool;
   a.ws = ws;
   a.out = out;
-  __shared__ __attribute__((aligned(1024))) char kbuf0[Smem<D>::kKBytes];
-  __shared__ __attribute__((aligned(1024))) char kbuf1[Smem<D>::kKBytes];
-  __shared__ __attribute__((aligned(16))) char part[Smem<D>::kPartBytes];
+  __shared__ __attribute__((aligned(1024))) char smem[Smem<D>::kBytes];
   __shared__ int s_next;
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
@@ -689,8 +705,8 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
     if (threadIdx.x == 0) nxt = atomicAdd(&ctrl[0], 1);
     const HfxItem it = items[idx];
     const HfxReq rq = reqs[it.req];
-    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, part);
-    else prefill_item<D>(a, H, it, rq, kbuf0, kbuf1);
+    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem);
+    else prefill_item<D>(a, H, it, rq, smem);
     if (threadIdx.x == 0) s_next = nxt;
     __syncthreads();
   }
