@@ -90,6 +90,9 @@ def main() -> int:
     ap.add_argument("--pool-copies", type=int, default=4, help="distinct KV pools rotated across steps")
     ap.add_argument("--no-paths", action="store_true", help="skip the decode-heavy / prefill-heavy steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference dispatches for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU; there is no sharded path to time (--gpus must be 1)",
@@ -106,6 +109,15 @@ def main() -> int:
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(7)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     b = synth.config(2)
     pools = [torch.from_numpy(b.pool.view(np.int16)).cuda()]
     for i in range(1, max(1, args.pool_copies)):
@@ -116,39 +128,39 @@ def main() -> int:
     # host cost of building + uploading the descriptor alone
     t0 = time.perf_counter()
     for i in range(50):
-        s = ring[i % len(ring)]
-        hb.hfx_build_batch_desc(s.shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, s.host_desc,
-                                s.device_desc, stream)
+        ring[i % len(ring)].build(stream)
         torch.cuda.synchronize()
     desc_us = (time.perf_counter() - t0) / 50 * 1e6
 
-    def one_step(i, ev=None):
-        s = ring[i % len(ring)]
-        if s.busy is not None:
-            s.busy.synchronize()        # the slot's previous upload and launch have drained
-        hb.hfx_build_batch_desc(s.shape, b.kind, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, s.host_desc,
-                                s.device_desc, stream)
-        if ev is not None:
-            ev[0].record(stream)
-        s.run(stream)
-        if ev is not None:
-            ev[1].record(stream)
-        s.busy = torch.cuda.Event()
-        s.busy.record(stream)
+    n_ev = args.steps
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    busy = [None] * len(ring)
 
-    for s in ring:
-        s.busy = None
+    def one_step(i, timed):
+        k = i % len(ring)
+        s = ring[k]
+        if busy[k] is not None:
+            busy[k].synchronize()        # the slot's previous upload and launch have drained
+        s.build(stream)
+        if timed:
+            ev0[i].record(stream)
+            s.run(stream)
+            ev1[i].record(stream)
+            busy[k] = ev1[i]
+        else:
+            s.run(stream)
+
     for i in range(args.warmup):
-        one_step(i)
+        one_step(i, False)
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        one_step(i, evs[i])
+        one_step(i, True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
-    launch_ms = [a.elapsed_time(c) for a, c in evs]
+    launch_ms = [a.elapsed_time(c) for a, c in zip(ev0, ev1)]
     launch_avg = sum(launch_ms) / len(launch_ms)
 
     T = b.total_q
@@ -164,7 +176,8 @@ def main() -> int:
                    "pool_copies_rotated": len(pools), "step": "descriptor build + upload + one persistent launch"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "mixed_attention_kernel<128>", "launch_ms_avg": round(launch_avg, 5),
+                     "kernel": "mixed_attention_kernel<128> (+ merge_kernel<128>, same API call)",
+                     "launch_ms_avg": round(launch_avg, 5),
                      "algorithmic_bytes": alg_bytes},
         "launch_only_tokens_per_s": round(T / launch_avg * 1e3, 1),
         "desc_build_upload_us": round(desc_us, 1),

@@ -191,7 +191,7 @@ class DescHeader(ctypes.Structure):
                 ("off_items", ctypes.c_uint32), ("off_groups", ctypes.c_uint32), ("n_ctrl", ctypes.c_uint32),
                 ("total_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
                 ("ws_off_ml", ctypes.c_uint64), ("max_group_rows", ctypes.c_int32),
-                ("reserved", ctypes.c_uint32 * 7)]
+                ("n_units", ctypes.c_int32), ("off_units", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 5)]
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
@@ -213,6 +213,7 @@ def parse_desc(host_desc: np.ndarray) -> dict:
         "bt": buf[h.off_bt:h.off_bt + 4 * h.n_bt].view(np.int32),
         "items": buf[h.off_items:h.off_items + ITEM_DTYPE.itemsize * h.n_items].view(ITEM_DTYPE),
         "groups": buf[h.off_groups:h.off_groups + GROUP_DTYPE.itemsize * h.n_groups].view(GROUP_DTYPE),
+        "units": buf[h.off_units:h.off_units + 8 * h.n_units].view(np.int32).reshape(-1, 2),
     }
 
 
@@ -220,12 +221,14 @@ def parse_desc(host_desc: np.ndarray) -> dict:
 # Device-memory plumbing for callers that hold a step as numpy arrays (tests, bench, smoke).
 # ------------------------------------------------------------------------------------------
 class DeviceStep:
-    """Owns the torch buffers of one step: descriptor (pinned host + device), workspace, Q, out."""
+    """Owns the torch buffers of one step (descriptor: pinned host + device; workspace; Q; out) and the
+    marshalled arguments of the two calls, so that build() and run() are one ctypes call each."""
 
     def __init__(self, batch, pool_dev=None, device="cuda:0", softmax_scale=0.0, stream=None):
         import torch
         self.torch = torch
         self.device = torch.device(device)
+        self.batch = batch
         self.shape = make_shape(batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.num_pages,
                                 softmax_scale)
         hb, db, wb = hfx_batch_desc_sizes(self.shape, batch.kind, batch.q_len, batch.ctx_len)
@@ -233,18 +236,47 @@ class DeviceStep:
         self.device_desc = torch.empty(db, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(max(wb, 16), dtype=torch.uint8, device=self.device)
         self.workspace_bytes = wb
-        self.pool = pool_dev if pool_dev is not None else torch.from_numpy(batch.pool.view(np.int16)).to(self.device)
+        self._pool = pool_dev if pool_dev is not None else torch.from_numpy(batch.pool.view(np.int16)).to(self.device)
         self.q = torch.from_numpy(batch.q.view(np.int16)).to(self.device)
         self.out = torch.zeros_like(self.q)
-        hfx_build_batch_desc(self.shape, batch.kind, batch.q_len, batch.ctx_len, batch.bt_indptr, batch.bt_pages,
-                             self.host_desc, self.device_desc, stream if stream is not None
-                             else torch.cuda.current_stream(self.device))
-        self.batch = batch
+        self._lib = load()
+        self._keep = [_i32(a) for a in (batch.kind, batch.q_len, batch.ctx_len, batch.bt_indptr, batch.bt_pages)]
+        self._build_args = (ctypes.byref(self.shape), len(self._keep[0][0]), *(p for _, p in self._keep),
+                            _ptr(self.host_desc), _nbytes(self.host_desc), _ptr(self.device_desc),
+                            _nbytes(self.device_desc))
+        self._set_run_args()
+        self.build(stream)
+
+    def _set_run_args(self):
+        self._run_args = (ctypes.byref(self.shape), _ptr(self.q), _ptr(self._pool), _ptr(self.host_desc),
+                          _ptr(self.device_desc), _ptr(self.workspace) if self.workspace_bytes else None,
+                          self.workspace_bytes, _ptr(self.out))
+
+    @property
+    def pool(self):
+        return self._pool
+
+    @pool.setter
+    def pool(self, value):
+        self._pool = value
+        self._set_run_args()
+
+    def _stream_ptr(self, stream):
+        if stream is None:
+            stream = self.torch.cuda.current_stream(self.device)
+        return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+    def build(self, stream=None):
+        """hfx_build_batch_desc: plan the step on the host and enqueue the descriptor upload."""
+        rc = self._lib.hfx_build_batch_desc(*self._build_args, self._stream_ptr(stream))
+        if rc != HFX_OK:
+            raise HfxError(rc, "hfx_build_batch_desc")
 
     def run(self, stream=None):
-        s = stream if stream is not None else self.torch.cuda.current_stream(self.device)
-        hfx_mixed_paged_attention(self.shape, self.q, self.pool, self.host_desc, self.device_desc,
-                                  self.workspace if self.workspace_bytes else None, self.out, s)
+        """hfx_mixed_paged_attention on the step's buffers."""
+        rc = self._lib.hfx_mixed_paged_attention(*self._run_args, self._stream_ptr(stream))
+        if rc != HFX_OK:
+            raise HfxError(rc, "hfx_mixed_paged_attention")
         return self.out
 
     def out_bits(self) -> np.ndarray:
@@ -256,7 +288,7 @@ class DeviceStep:
         c = int(self.batch.ctx_len[request])
         k = t.zeros((c, self.batch.num_kv_heads, self.batch.head_dim), dtype=t.int16, device=self.device)
         v = t.zeros_like(k)
-        hfx_gather_kv(self.shape, self.pool, self.host_desc, self.device_desc, request, k, v,
+        hfx_gather_kv(self.shape, self._pool, self.host_desc, self.device_desc, request, k, v,
                       t.cuda.current_stream(self.device))
         t.cuda.synchronize(self.device)
         return k.cpu().numpy().view(np.uint16), v.cpu().numpy().view(np.uint16)

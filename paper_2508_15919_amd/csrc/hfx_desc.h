@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 7u
+#define HFX_DESC_VERSION 8u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -27,7 +27,9 @@ struct HfxHeader {
   uint64_t workspace_bytes;
   uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */
   int32_t max_group_rows;       /* largest rows_per_split over the groups */
-  uint32_t reserved[7];
+  int32_t n_units;              /* merge work units (one workgroup each) */
+  uint32_t off_units;
+  uint32_t reserved[5];
 };
 
 struct HfxReq {
@@ -54,6 +56,12 @@ struct HfxItem {
 // One merge group: nsplit partials of rows_per_split rows each, split s at workspace rows
 // base_row + s * rows_per_split.  type/req/h0/hn/row0 are those of the group's items and say
 // which output rows the merged result belongs to.
+// One workgroup of the merge launch: 8 / lanes rows of a group starting at row chunk * (8 / lanes),
+// where lanes (8 or 1) is how many threads share the splits of one row.
+struct HfxUnit {
+  int32_t group, chunk;
+};
+
 struct HfxGroup {
   int32_t nsplit;
   int32_t base_row;

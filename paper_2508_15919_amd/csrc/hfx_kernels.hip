@@ -59,51 +59,42 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 
 // ----------------------------------------------------------------------------------------------
 // Split merge (runs as its own small launch after the persistent kernel, so the partials are
-// ordered by the kernel boundary and no fences or arrival counters are needed).  Workgroup
-// (group, chunk) combines kMergeRows rows of the group's partials (m, l, acc):
+// ordered by the kernel boundary and no fences or arrival counters are needed).  One workgroup
+// per merge unit combines a few rows of a group's partials (m, l, acc):
 //   m* = max m_s,  l* = sum l_s 2^(m_s - m*),  out = sum acc_s 2^(m_s - m*) / l*
-// (m is kept in the base-2 domain throughout), rounds to bf16 and stores.  The splits of a row
-// are spread over 8 lanes of threads so that their loads are all in flight together.
+// (m is kept in the base-2 domain throughout), rounds to bf16 and stores.  A thread owns one
+// float4 column of a row; for groups with many splits 8 threads share the splits of that column
+// (one row per workgroup) so that all loads are in flight together, for groups with at most 8
+// splits one thread takes them all (8 rows per workgroup).
 // ----------------------------------------------------------------------------------------------
-constexpr int kMergeSplitLanes = 8;
-template <int D>
-struct MergeShape {
-  static constexpr int kCols = D / 4;                                           // float4 columns of a row
-  static constexpr int kRows = HFX_WG_THREADS / (kCols * kMergeSplitLanes);     // rows per workgroup
-};
-
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __restrict__ desc,
                                                                const float* __restrict__ ws,
                                                                __bf16* __restrict__ out) {
-  KArgs a;
-  a.desc = desc;
-  a.q = nullptr;
-  a.pool = nullptr;
-  a.ws = const_cast<float*>(ws);
-  a.out = out;
-  constexpr int C4 = MergeShape<D>::kCols, RB = MergeShape<D>::kRows, SL = kMergeSplitLanes;
-  __shared__ float s_max[RB][SL];
-  __shared__ float s_l[RB][SL];
-  __shared__ f32x4 s_acc[RB][SL][C4];
-  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
-  const HfxGroup gr = reinterpret_cast<const HfxGroup*>(a.desc + H->off_groups)[blockIdx.x];
-  if ((int)blockIdx.y * RB >= gr.rows_per_split) return;
-  const HfxReq rq = reinterpret_cast<const HfxReq*>(a.desc + H->off_req)[gr.req];
+  constexpr int C4 = D / 4;                       // float4 columns of a row
+  constexpr int Q = HFX_WG_THREADS / C4;          // threads per column: 8 (D = 128) or 16 (D = 64)
+  __shared__ float s_max[Q];
+  __shared__ float s_l[Q];
+  __shared__ f32x4 s_acc[Q][C4];
+  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(desc);
+  const HfxUnit un = reinterpret_cast<const HfxUnit*>(desc + H->off_units)[blockIdx.x];
+  const HfxGroup gr = reinterpret_cast<const HfxGroup*>(desc + H->off_groups)[un.group];
+  const HfxReq rq = reinterpret_cast<const HfxReq*>(desc + H->off_req)[gr.req];
   const int tid = threadIdx.x;
-  const int col = tid % C4, sl = (tid / C4) % SL, rl = tid / (C4 * SL);
-  const int row = blockIdx.y * RB + rl;
-  const bool row_ok = row < gr.rows_per_split;
+  const int col = tid % C4, q = tid / C4;
+  const bool wide = gr.nsplit > 8;                // Q... only the first 8 thread rows are used below
+  const int SL = wide ? 8 : 1;                    // threads sharing one row's splits
+  const int sl = wide ? q : 0;
+  const int row = wide ? un.chunk : un.chunk * 8 + q;
+  const bool row_ok = q < 8 && row < gr.rows_per_split;
   const int Hq = H->num_q_heads;
   const int G = Hq / H->num_kv_heads;
-  const float* acc = a.ws;
-  const float* ml = reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.ws) + H->ws_off_ml);
+  const float* ml = reinterpret_cast<const float*>(reinterpret_cast<const char*>(ws) + H->ws_off_ml);
   const int rows = gr.rows_per_split, ns = gr.nsplit, base = gr.base_row;
-  constexpr int kMax = (64 + SL - 1) / SL;      // the planner never makes more than 64 splits
-  float mv[kMax], lv[kMax];
+  float mv[8], lv[8];
   float mloc = NEG_INF;
 #pragma unroll
-  for (int i = 0; i < kMax; ++i) {
+  for (int i = 0; i < 8; ++i) {                   // the planner never makes more than 64 splits
     const int s = sl + i * SL;
     mv[i] = NEG_INF;
     lv[i] = 0.f;
@@ -114,27 +105,37 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __res
     }
     mloc = fmaxf(mloc, mv[i]);
   }
-  if (col == 0) s_max[rl][sl] = mloc;
-  __syncthreads();
-  float mm = NEG_INF;
+  float mm = mloc;
+  if (wide) {
+    if (col == 0) s_max[q] = mloc;
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < SL; ++i) mm = fmaxf(mm, s_max[rl][i]);
+    for (int i = 0; i < 8; ++i) mm = fmaxf(mm, s_max[i]);
+  }
   float ll = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i = 0; i < kMax; ++i) {
+  for (int i = 0; i < 8; ++i) {
     const int s = sl + i * SL;
     if (row_ok && s < ns) {
       const long pr = (long)base + (long)s * rows + row;
       const float w = fast_exp2(mv[i] - mm);
       ll += lv[i] * w;
-      o += *reinterpret_cast<const f32x4*>(acc + pr * D + col * 4) * w;
+      o += *reinterpret_cast<const f32x4*>(ws + pr * D + col * 4) * w;
     }
   }
-  s_acc[rl][sl][col] = o;
-  if (col == 0) s_l[rl][sl] = ll;
-  __syncthreads();
-  if (sl != 0 || !row_ok) return;
+  if (wide) {
+    s_acc[q][col] = o;
+    if (col == 0) s_l[q] = ll;
+    __syncthreads();
+    if (q != 0) return;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+      o += s_acc[i][col];
+      ll += s_l[i];
+    }
+  }
+  if (!row_ok) return;
   long orow;
   if (gr.type == HFX_ITEM_DECODE) {
     orow = (long)rq.q_start * Hq + gr.h0 * G + row;
@@ -145,16 +146,11 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __res
     if (qrow >= rq.q_len) return;
     orow = ((long)rq.q_start + qrow) * Hq + head;
   }
-#pragma unroll
-  for (int i = 1; i < SL; ++i) {
-    o += s_acc[rl][i][col];
-    ll += s_l[rl][i];
-  }
   const float inv = 1.0f / ll;
   bf16x4 ob;
 #pragma unroll
   for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[e] * inv);
-  *reinterpret_cast<bf16x4*>(a.out + orow * D + col * 4) = ob;
+  *reinterpret_cast<bf16x4*>(out + orow * D + col * 4) = ob;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -747,8 +743,7 @@ hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
 }
 
-hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, int max_group_rows, unsigned off_ctrl,
-                                  void* desc, const void* q, const void* pool, void* ws, void* out,
+hipError_t launch_mixed_attention(int head_dim, int grid, int n_units, unsigned off_ctrl, void* desc, const void* q, const void* pool, void* ws, void* out,
                                   hipStream_t stream) {
   const char* d = static_cast<const char*>(desc);
   int* ctrl = reinterpret_cast<int*>(static_cast<char*>(desc) + off_ctrl);
@@ -760,14 +755,11 @@ hipError_t launch_mixed_attention(int head_dim, int grid, int n_groups, int max_
     hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
   else
     hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
-  if (n_groups > 0) {
-    if (head_dim == 128) {
-      const int chunks = (max_group_rows + MergeShape<128>::kRows - 1) / MergeShape<128>::kRows;
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
-    } else {
-      const int chunks = (max_group_rows + MergeShape<64>::kRows - 1) / MergeShape<64>::kRows;
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_groups, chunks), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
-    }
+  if (n_units > 0) {
+    if (head_dim == 128)
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
+    else
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
   }
   return hipGetLastError();
 }

@@ -183,6 +183,16 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   P.n_partial_rows = (int32_t)rows;
   std::stable_sort(P.items.begin(), P.items.end(),
                    [](const HfxItem& a, const HfxItem& b) { return a.cost > b.cost; });
+  // merge work units: groups with many splits get 8 threads per (row, column) and one row per
+  // workgroup, groups with few splits one thread per (row, column) and 8 rows per workgroup
+  P.units.clear();
+  for (size_t gi = 0; gi < P.groups.size(); ++gi) {
+    const int rows_per_unit = P.groups[gi].nsplit > 8 ? 1 : 8;
+    for (int c = 0; c * rows_per_unit < P.groups[gi].rows_per_split; ++c) {
+      HfxUnit u = {(int32_t)gi, c};
+      P.units.push_back(u);
+    }
+  }
   P.n_decode_items = P.n_prefill_items = 0;
   for (const HfxItem& it : P.items) (it.type == HFX_ITEM_DECODE ? P.n_decode_items : P.n_prefill_items)++;
   return HFX_OK;
@@ -221,7 +231,10 @@ void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
   h->off_items = (uint32_t)off;
   off = align_up(off + sizeof(HfxItem) * P.items.size(), 64);
   h->off_groups = (uint32_t)off;
-  off = align_up(off + sizeof(HfxGroup) * P.groups.size(), 256);
+  off = align_up(off + sizeof(HfxGroup) * P.groups.size(), 64);
+  h->off_units = (uint32_t)off;
+  h->n_units = (int32_t)P.units.size();
+  off = align_up(off + sizeof(HfxUnit) * P.units.size(), 256);
   h->total_bytes = off;
   uint64_t acc_bytes = align_up((uint64_t)P.n_partial_rows * shape->head_dim * 4ull, 256);
   h->ws_off_ml = acc_bytes;
@@ -255,6 +268,7 @@ hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, 
     std::memcpy(bt + P.reqs[(size_t)r].bt_start, bt_pages + bt_indptr[r], 4ull * (size_t)P.reqs[(size_t)r].n_pages);
   std::memcpy(base + h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size());
   if (!P.groups.empty()) std::memcpy(base + h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size());
+  if (!P.units.empty()) std::memcpy(base + h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size());
   return HFX_OK;
 }
 

@@ -13,6 +13,7 @@ struct Plan {
   std::vector<HfxReq> reqs;
   std::vector<HfxItem> items;
   std::vector<HfxGroup> groups;
+  std::vector<HfxUnit> units;
   int32_t total_q = 0, n_bt = 0, n_partial_rows = 0, n_decode_items = 0, n_prefill_items = 0;
 };
 

@@ -105,6 +105,12 @@ def check_coverage(b, d):
                 assert it["slot_row"] == -1
     if h.n_groups:
         assert np.array_equal(group_count[:h.n_groups], groups["nsplit"]) and np.all(groups["nsplit"] > 1)
+        # merge units: every row of every group belongs to exactly one unit
+        seen = [np.zeros(g["rows_per_split"], np.int32) for g in groups]
+        for gi, chunk in d["units"]:
+            per = 1 if groups[gi]["nsplit"] > 8 else 8
+            seen[gi][chunk * per:(chunk + 1) * per] += 1
+        assert all(np.all(x == 1) for x in seen) and h.n_units == len(d["units"])
         assert np.all(slot_owner[:h.n_partial_rows] == 1)
         assert h.workspace_bytes >= h.ws_off_ml + 8 * h.n_partial_rows >= 4 * h.n_partial_rows * b.head_dim
     else:
