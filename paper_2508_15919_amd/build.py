@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhfxattn.so")
 SOURCES = ["hfx_kernels.hip", "hfx_api.cpp", "hfx_plan.cpp"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
+# -fno-honor-nans: no floating-point operation in the kernels is ever fed a NaN (possibly-NaN scores
+# are masked through integer selects first), and without it every max carries a canonicalising twin.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

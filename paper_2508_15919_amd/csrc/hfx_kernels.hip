@@ -42,6 +42,16 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
+// `x` where keep, -inf elsewhere, as a select on the bit pattern: the scores of masked keys may be
+// NaN (unused slots hold anything), and the file is compiled with -fno-honor-nans, under which a
+// floating-point select of a NaN is not defined.
+__device__ __forceinline__ float keep_or_neg_inf(float x, bool keep) {
+  const unsigned u = keep ? __builtin_bit_cast(unsigned, x) : 0xff800000u;
+  return __builtin_bit_cast(float, u);
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 // Exchange between lane n and lane n ^ 32.
 __device__ __forceinline__ float max_xor32(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
 __device__ __forceinline__ float sum_xor32(float x) { return x + __shfl_xor(x, 32, 64); }
@@ -200,7 +210,7 @@ __device__ __forceinline__ void decode_compute(PairRegs<D>& r, const bf16x8* qf,
   }
   if (nv < 8) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s[e] = (e < nv) ? s[e] : NEG_INF;
+    for (int e = 0; e < 8; ++e) s[e] = keep_or_neg_inf(s[e], e < nv);
   }
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
   mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -457,12 +467,12 @@ __device__ __forceinline__ void softmax_block(f32x16& s, PrefillWave<D>& w, bf16
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int key = key0 + (v >> 3) * 16 + (v & 7);
-      s[v] = key <= w.pos ? s[v] : NEG_INF;
+      s[v] = keep_or_neg_inf(s[v], key <= w.pos);
     }
   }
   float mx = fmaxf(s[0], s[1]);
 #pragma unroll
-  for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(s[v], s[v + 1]));
+  for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);   // v_max3_f32
   mx = max_xor32(mx) * sl2;
   if (__any(mx > w.m + 8.0f)) {
     const float mn = fmaxf(w.m, mx);
@@ -473,12 +483,20 @@ __device__ __forceinline__ void softmax_block(f32x16& s, PrefillWave<D>& w, bf16
     w.m = mn;
   }
   const float mneg = w.m == NEG_INF ? 0.f : -w.m;
+  // weights rounded to bf16 in pairs; their sum is taken over the rounded values (the ones the
+  // second contraction uses) with one dot-product instruction per pair
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
   float ps = 0.f;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const float pv = fast_exp2(__builtin_fmaf(s[v], sl2, mneg));
-    ps += pv;
-    pb[v >> 3][v & 7] = (__bf16)pv;
+  for (int v = 0; v < 16; v += 2) {
+    bf16x2 pk;
+    pk[0] = (__bf16)fast_exp2(__builtin_fmaf(s[v], sl2, mneg));
+    pk[1] = (__bf16)fast_exp2(__builtin_fmaf(s[v + 1], sl2, mneg));
+    ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
+    pb[v >> 3][v & 7] = pk[0];
+    pb[v >> 3][(v & 7) + 1] = pk[1];
   }
   w.l += ps;
 }
