@@ -196,6 +196,26 @@ hfx_status hfx_gather_kv(const hfx_shape* shape, const void* kv_pool,
                          const void* host_desc, const void* device_desc,
                          int32_t request, void* k_out, void* v_out, void* stream);
 
+/*
+ * Writes the step's new keys and values into the page pool: the step just
+ * before the attention of a scheduled step (Section 3.4: the instance's
+ * execution loop fills its block-managed KV cache as tokens are processed;
+ * Section 3.3.1: each request contributes q_len new tokens).  For request r the
+ * chunk's rows i in [0, q_len[r]) are the logical tokens ctx_len[r] - q_len[r] + i;
+ * token t goes to page bt_pages[bt_indptr[r] + t / 16], slot t % 16, in the pool
+ * layout described above.  A pure byte move (bit-exact).
+ *   k_new, v_new [device] bf16 [T][Hkv][D], rows packed like Q
+ *   kv_pool      [device] the page pool, written in place
+ *   host_desc / device_desc: the step's descriptor, as for the attention call
+ * Pages shared between requests must not be written by two requests of the same
+ * step (the caller's block manager guarantees this; it is not checked).
+ * Asynchronous on `stream`; allocates nothing.
+ * Errors: HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_DESC, HFX_ERR_ALIGN, HFX_ERR_DEVICE.
+ */
+hfx_status hfx_append_kv(const hfx_shape* shape, const void* k_new, const void* v_new,
+                         void* kv_pool, const void* host_desc, const void* device_desc,
+                         void* stream);
+
 #ifdef __cplusplus
 }
 #endif

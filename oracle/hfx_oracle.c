@@ -244,3 +244,30 @@ int hfx_oracle_gather_kv(int Hkv, int D, long num_pages, int R, const int32_t* c
   }
   return 0;
 }
+
+/* Writes the new tokens of every request into the pool (in place): chunk row i of request r is
+ * logical token ctx_len - q_len + i (Section 3.4: the engine loop fills the block-managed cache;
+ * Section 3.3.1: q_len new tokens per request).  k_new, v_new: uint16 [T][Hkv][D]. */
+int hfx_oracle_append_kv(int Hkv, int D, long num_pages, int R, const int32_t* q_len,
+                         const int32_t* ctx_len, const int32_t* bt_indptr, const int32_t* bt_pages,
+                         const uint16_t* k_new, const uint16_t* v_new, uint16_t* pool) {
+  if (D <= 0 || D % 16 != 0 || Hkv <= 0) return -2;
+  orc_ctx c = {Hkv, Hkv, D, num_pages, bt_indptr, bt_pages, pool};
+  long row = 0;
+  for (int r = 0; r < R; ++r) {
+    if (q_len[r] < 1 || ctx_len[r] < q_len[r]) return -4;
+    for (int i = 0; i < q_len[r]; ++i, ++row) {
+      long t = (long)ctx_len[r] - q_len[r] + i;
+      long page = bt_pages[bt_indptr[r] + t / ORC_PAGE];
+      if (page < 0 || page >= num_pages) return -6;
+      int slot = (int)(t % ORC_PAGE);
+      for (int g = 0; g < Hkv; ++g)
+        for (int d = 0; d < D; ++d) {
+          size_t src = ((size_t)row * Hkv + g) * D + d;
+          pool[block_base(&c, page, g, 0) + k_offset(slot, d)] = k_new[src];
+          pool[block_base(&c, page, g, 1) + (size_t)d * ORC_PAGE + slot] = v_new[src];
+        }
+    }
+  }
+  return 0;
+}

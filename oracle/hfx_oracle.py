@@ -44,6 +44,9 @@ def _load():
         lib.hfx_oracle_gather_kv.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_int,
                                              i32p, i32p, i32p, u16p, ctypes.c_int, u16p, u16p]
         lib.hfx_oracle_gather_kv.restype = ctypes.c_int
+        lib.hfx_oracle_append_kv.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_int, i32p, i32p,
+                                             i32p, i32p, u16p, u16p, u16p]
+        lib.hfx_oracle_append_kv.restype = ctypes.c_int
         lib.hfx_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -129,3 +132,19 @@ def attention_batch(b, scale=0.0):
 def attention_rows_batch(b, sample_req, sample_row, sample_head, scale=0.0):
     return attention_rows(b.num_q_heads, b.num_kv_heads, b.head_dim, b.num_pages, b.kind, b.q_len, b.ctx_len,
                           b.bt_indptr, b.bt_pages, b.q, b.pool, sample_req, sample_row, sample_head, scale)
+
+
+def append_kv(Hkv, D, num_pages, q_len, ctx_len, bt_indptr, bt_pages, k_new, v_new, pool):
+    """Writes the chunk tokens' K/V (uint16 [T, Hkv, D]) into `pool` in place (pool must be a contiguous
+    uint16 array)."""
+    ql, pql = _i32(q_len)
+    cl, pcl = _i32(ctx_len)
+    bi, pbi = _i32(bt_indptr)
+    bp, pbp = _i32(bt_pages)
+    kn, pkn = _u16(k_new)
+    vn, pvn = _u16(v_new)
+    assert pool.dtype == np.uint16 and pool.flags.c_contiguous
+    rc = _load().hfx_oracle_append_kv(int(Hkv), int(D), int(num_pages), len(ql), pql, pcl, pbi, pbp, pkn, pvn,
+                                      pool.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the inputs (code {rc})")

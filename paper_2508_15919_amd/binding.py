@@ -20,7 +20,7 @@ HFX_ERR_PAGE_ID, HFX_ERR_BUFSIZE, HFX_ERR_DEVICE, HFX_ERR_DESC, HFX_ERR_ALIGN = 
 HFX_DECODE, HFX_PREFILL = 0, 1
 
 EXPORTS = ["hfx_status_string", "hfx_version", "hfx_batch_desc_sizes", "hfx_build_batch_desc",
-           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv"]
+           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv", "hfx_append_kv"]
 
 
 class hfx_shape(ctypes.Structure):
@@ -65,6 +65,8 @@ def load() -> ctypes.CDLL:
         lib.hfx_mixed_paged_attention.restype = ctypes.c_int32
         lib.hfx_gather_kv.argtypes = [shp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
         lib.hfx_gather_kv.restype = ctypes.c_int32
+        lib.hfx_append_kv.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        lib.hfx_append_kv.restype = ctypes.c_int32
         _lib = lib
     return _lib
 
@@ -175,6 +177,13 @@ def hfx_gather_kv(shape: hfx_shape, kv_pool, host_desc, device_desc, request: in
         raise HfxError(rc, "hfx_gather_kv")
 
 
+def hfx_append_kv(shape: hfx_shape, k_new, v_new, kv_pool, host_desc, device_desc, stream=None) -> None:
+    rc = load().hfx_append_kv(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(kv_pool), _ptr(host_desc),
+                              _ptr(device_desc), _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_append_kv")
+
+
 # ------------------------------------------------------------------------------------------
 # Read-only views of a descriptor blob, for inspection and for the planner's CPU tests.
 # They mirror csrc/hfx_desc.h.
@@ -195,7 +204,8 @@ class DescHeader(ctypes.Structure):
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
-                                               "kb", "ke", "cost", "pad")])
+                                               "kb", "ke", "cost", "pad", "rq_kind", "rq_q_len", "rq_ctx_len",
+                                               "rq_q_start", "rq_bt_start", "rq_n_pages", "rq_pad0", "rq_pad1")])
 REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
                                               "pad0", "pad1")])
 GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "type", "req", "h0", "hn",

@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 8u
+#define HFX_DESC_VERSION 9u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -47,10 +47,13 @@ struct HfxReq {
 //           nrows = rows covered (32 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
 //  group >= 0: the item is one of several splits; its partial goes to workspace rows
 //           [slot_row, slot_row + rows) and the merge kernel combines the group afterwards.
+//  The request's record is repeated inside the item so that a workgroup needs one dependent load
+//  less between taking a ticket and issuing its first KV load.
 struct HfxItem {
   int32_t type, req, group, slot_row;
   int32_t h0, hn, row0, nrows;
   int32_t kb, ke, cost, pad;
+  HfxReq rq;
 };
 
 // One merge group: nsplit partials of rows_per_split rows each, split s at workspace rows

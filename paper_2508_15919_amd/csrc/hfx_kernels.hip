@@ -707,7 +707,6 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   __shared__ int s_next;
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
-  const HfxReq* reqs = reinterpret_cast<const HfxReq*>(a.desc + H->off_req);
   const int n_items = H->n_items;
   if (threadIdx.x == 0) s_next = atomicAdd(&ctrl[0], 1);
   __syncthreads();
@@ -718,7 +717,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
     int nxt = 0;
     if (threadIdx.x == 0) nxt = atomicAdd(&ctrl[0], 1);
     const HfxItem it = items[idx];
-    const HfxReq rq = reqs[it.req];
+    const HfxReq rq = it.rq;
     if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem);
     else prefill_item<D>(a, H, it, rq, smem);
     if (threadIdx.x == 0) s_next = nxt;
@@ -751,6 +750,42 @@ __global__ void gather_kv_kernel(const char* desc, const uint16_t* pool, int req
     const long blk = ((pg * Hkv + g) * 2) * (16L * D);
     k_out[i] = pool[blk + ((long)(d / 16) * HFX_PAGE + slot) * 16 + d % 16];
     v_out[i] = pool[blk + 16L * D + (long)d * HFX_PAGE + slot];
+  }
+}
+
+// KV append: one thread per 16-byte piece (8 dimensions) of one new token's K or V for one kv-head.
+// K pieces land as 16 contiguous bytes of the page's K block (blocked by 16 dimensions); V pieces
+// scatter as eight 2-byte stores down a column of the dimension-major V block.
+__global__ void append_kv_kernel(const char* __restrict__ desc, const uint16_t* __restrict__ k_new,
+                                 const uint16_t* __restrict__ v_new, uint16_t* __restrict__ pool) {
+  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(desc);
+  const HfxReq* reqs = reinterpret_cast<const HfxReq*>(desc + H->off_req);
+  const int* bt_all = reinterpret_cast<const int*>(desc + H->off_bt);
+  const int Hkv = H->num_kv_heads, D = H->head_dim, R = H->num_requests;
+  const int pieces = D / 8;
+  const long total = (long)H->total_q * Hkv * pieces;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int pc = (int)(i % pieces);
+    const int g = (int)((i / pieces) % Hkv);
+    const int row = (int)(i / ((long)pieces * Hkv));
+    // request owning packed row `row`: binary search over q_start
+    int lo = 0, hi = R - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (reqs[mid].q_start <= row) lo = mid; else hi = mid - 1;
+    }
+    const HfxReq rq = reqs[lo];
+    const int t = rq.ctx_len - rq.q_len + (row - rq.q_start);
+    const long pg = bt_all[rq.bt_start + t / HFX_PAGE];
+    const int slot = t % HFX_PAGE;
+    const long blk = ((pg * Hkv + g) * 2) * (16L * D);
+    const long src = ((long)row * Hkv + g) * D + pc * 8;
+    const int d0 = pc * 8;
+    u32x4 kv = *reinterpret_cast<const u32x4*>(k_new + src);
+    *reinterpret_cast<u32x4*>(pool + blk + ((long)(d0 / 16) * HFX_PAGE + slot) * 16 + d0 % 16) = kv;
+    uint16_t* vdst = pool + blk + 16L * D + (long)d0 * HFX_PAGE + slot;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vdst[e * HFX_PAGE] = v_new[src + e];
   }
 }
 
@@ -790,6 +825,17 @@ hipError_t launch_gather_kv(const void* desc, const void* pool, int request, lon
   hipLaunchKernelGGL(gather_kv_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                      static_cast<const char*>(desc), static_cast<const uint16_t*>(pool), request,
                      static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out));
+  return hipGetLastError();
+}
+
+hipError_t launch_append_kv(const void* desc, const void* k_new, const void* v_new, void* pool, long pieces,
+                            hipStream_t stream) {
+  long blocks = (pieces + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     static_cast<const char*>(desc), static_cast<const uint16_t*>(k_new),
+                     static_cast<const uint16_t*>(v_new), static_cast<uint16_t*>(pool));
   return hipGetLastError();
 }
 

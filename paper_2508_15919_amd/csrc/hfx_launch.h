@@ -10,4 +10,7 @@ hipError_t launch_mixed_attention(int head_dim, int grid, int n_units, unsigned 
 hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
                             void* v_out, hipStream_t stream);
 
+hipError_t launch_append_kv(const void* desc, const void* k_new, const void* v_new, void* pool, long pieces,
+                            hipStream_t stream);
+
 }  // namespace hfx

@@ -193,6 +193,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       P.units.push_back(u);
     }
   }
+  for (HfxItem& it : P.items) it.rq = P.reqs[(size_t)it.req];
   P.n_decode_items = P.n_prefill_items = 0;
   for (const HfxItem& it : P.items) (it.type == HFX_ITEM_DECODE ? P.n_decode_items : P.n_prefill_items)++;
   return HFX_OK;

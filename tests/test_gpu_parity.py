@@ -181,6 +181,26 @@ def test_custom_softmax_scale(hb, oracle):
     assert np.abs(got - ref).max() <= MAX_ABS
 
 
+@pytest.mark.parametrize("idx,scale", [(1, 1.0), (2, 0.25), (5, 0.05)])
+def test_append_kv_is_bit_exact_and_feeds_attention(hb, oracle, idx, scale):
+    import torch
+    b = synth.config(idx, scale)
+    rng = np.random.default_rng(idx)
+    T, Hkv, D = b.total_q, b.num_kv_heads, b.head_dim
+    k_new = synth.f32_to_bf16_bits(rng.standard_normal((T, Hkv, D)).astype(np.float32))
+    v_new = synth.f32_to_bf16_bits(rng.standard_normal((T, Hkv, D)).astype(np.float32))
+    step = hb.DeviceStep(b)
+    hb.hfx_append_kv(step.shape, torch.from_numpy(k_new.view(np.int16)).cuda(), torch.from_numpy(v_new.view(np.int16)).cuda(),
+                     step.pool, step.host_desc, step.device_desc, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    oracle.append_kv(Hkv, D, b.num_pages, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, k_new, v_new, b.pool)
+    assert np.array_equal(step.pool.cpu().numpy().view(np.uint16), b.pool), "pool after append must match bit for bit"
+    step.run()
+    got = bf16_bits_to_f64(step.out_bits())
+    err = np.abs(got - oracle.attention_batch(b))
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
 def test_device_side_errors(hb):
     import torch
     b = synth.config(1)

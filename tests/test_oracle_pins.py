@@ -253,6 +253,31 @@ def test_gather_recovers_tokens_written_one_by_one(oracle):
     assert np.array_equal(gk, f32_to_bf16_bits(k)) and np.array_equal(gv, f32_to_bf16_bits(v))
 
 
+def test_append_writes_exactly_the_chunk_tokens(oracle):
+    # pinned by the independent numpy un-paging: after the append the chunk's tokens read back as the
+    # new K/V, and every other element of the pool is untouched
+    b = small_mixed(23, Hq=8, Hkv=2, D=64)
+    rng = np.random.default_rng(4)
+    T = b.total_q
+    k_new = f32_to_bf16_bits(rng.standard_normal((T, 2, 64)).astype(np.float32))
+    v_new = f32_to_bf16_bits(rng.standard_normal((T, 2, 64)).astype(np.float32))
+    before = b.pool.copy()
+    oracle.append_kv(2, 64, b.num_pages, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, k_new, v_new, b.pool)
+    qi = b.q_indptr()
+    touched = np.zeros(b.pool.shape, bool)
+    for r in range(b.num_requests):
+        c, ql = int(b.ctx_len[r]), int(b.q_len[r])
+        k, v = brute.unpage(b, r)
+        assert np.array_equal(k[c - ql:], bf16_bits_to_f64(k_new[qi[r]:qi[r + 1]]))
+        assert np.array_equal(v[c - ql:], bf16_bits_to_f64(v_new[qi[r]:qi[r + 1]]))
+        for t in range(c - ql, c):
+            pg = b.bt_pages[b.bt_indptr[r] + t // 16]
+            touched[pg, :, 0].reshape(2, 4, 16, 16)[:, :, t % 16, :] = True
+            touched[pg, :, 1].reshape(2, 64, 16)[:, :, t % 16] = True
+    assert np.array_equal(b.pool[~touched], before[~touched])
+    assert touched.sum() == 2 * T * 2 * 64
+
+
 def test_split_merge_identity_in_fp64():
     # (m, l, acc) partials over any partition of the keys merge to the one-pass result.
     rng = np.random.default_rng(6)
