@@ -57,29 +57,54 @@ def time_launches(torch, hb, step, pools, iters, warmup):
     return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
 
 
-def path_figures(torch, hb, synth, which, iters, warmup):
-    """Decode-heavy (which=3) or prefill-heavy (which=4) step, attention launches only."""
-    b = synth.config(which, fill_pool=False)
-    if which == 4:
-        b = b.sub_batch(synth.PREFILL)
-    pools = device_pool(torch, b, 1000 + which, copies=1 if which == 3 else 2)
-    step = hb.DeviceStep(b, pool_dev=pools[0])
+def path_figures(torch, hb, batch, pools, iters, warmup):
+    """Attention launches only of one step: time, and the figures of whichever kinds of work it holds."""
+    step = hb.DeviceStep(batch, pool_dev=pools[0])
     avg, med, best = time_launches(torch, hb, step, pools, iters, warmup)
-    out = {"workload": b.name, "requests": b.num_requests, "query_tokens": b.total_q,
-           "launch_ms_avg": round(avg, 4), "launch_ms_median": round(med, 4), "launch_ms_min": round(best, 4)}
-    if which == 3:
-        byt = b.decode_io_bytes()
+    out = {"workload": batch.name, "requests": batch.num_requests, "query_tokens": batch.total_q,
+           "launch_ms_avg": round(avg, 4), "launch_ms_median": round(med, 4), "launch_ms_min": round(best, 4),
+           "tokens_per_s": round(batch.total_q / avg * 1e3, 1)}
+    n_dec = int((batch.kind == 0).sum())
+    if n_dec == batch.num_requests:
+        byt = batch.decode_io_bytes()
         out.update(bound="hbm", algorithmic_bytes=byt, achieved_GBs=round(byt / avg / 1e6, 1),
                    frac_of_hbm_peak=round(byt / avg / 1e6 / HBM_PEAK_GBS, 4),
-                   kv_tokens_per_s=round(float(b.ctx_len.sum()) / avg * 1e3, 1))
-    else:
-        fl = b.prefill_flops()
+                   kv_tokens_per_s=round(float(batch.ctx_len.sum()) / avg * 1e3, 1))
+    elif n_dec == 0:
+        fl = batch.prefill_flops()
         out.update(bound="mfma", algorithmic_flops=fl, achieved_TFLOPs=round(fl / avg / 1e9, 1),
-                   frac_of_bf16_mfma_peak=round(fl / avg / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
-                   tokens_per_s=round(b.total_q / avg * 1e3, 1))
-    del step, pools
-    torch.cuda.empty_cache()
+                   frac_of_bf16_mfma_peak=round(fl / avg / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4))
+    else:
+        byt = batch.decode_io_bytes() + batch.prefill_io_bytes()
+        out.update(algorithmic_bytes=byt, achieved_GBs=round(byt / avg / 1e6, 1),
+                   algorithmic_flops=batch.prefill_flops())
+    del step
     return out
+
+
+def append_figures(torch, hb, batch, pool, iters, warmup):
+    """hfx_append_kv of the step's chunk tokens (the call that precedes the attention of a step)."""
+    step = hb.DeviceStep(batch, pool_dev=pool)
+    T, Hkv, D = batch.total_q, batch.num_kv_heads, batch.head_dim
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    k_new = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    v_new = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        step.append(k_new, v_new, stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, c in evs:
+        a.record(stream)
+        step.append(k_new, v_new, stream)
+        c.record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(c) for a, c in evs)
+    avg = sum(ms) / len(ms)
+    byt = 2 * (2 * T * Hkv * D * 2)        # K and V, read once and written once
+    return {"workload": batch.name + "/append", "tokens": T, "launch_ms_avg": round(avg, 5),
+            "launch_ms_min": round(ms[0], 5), "bound": "hbm", "algorithmic_bytes": byt,
+            "achieved_GBs": round(byt / avg / 1e6, 1)}
 
 
 def main() -> int:
@@ -205,15 +230,53 @@ def main() -> int:
         result["parity_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
 
     if not args.no_paths:
+        paths = {}
+
+        def leg(name, fn):
+            try:
+                paths[name] = fn()
+            except Exception as e:  # the headline above stands on its own
+                paths[name] = {"error": repr(e)}
+
+        # the two pure steps hidden in the headline step (the paper's E_d and E_p), over the same pools
+        leg("cfg2_decode_only", lambda: path_figures(torch, hb, b.sub_batch(synth.DECODE), pools, 100, 10))
+        leg("cfg2_prefill_only", lambda: path_figures(torch, hb, b.sub_batch(synth.PREFILL), pools, 100, 10))
+        if all("launch_ms_avg" in paths[k] for k in ("cfg2_decode_only", "cfg2_prefill_only")):
+            td, tp = paths["cfg2_decode_only"]["launch_ms_avg"], paths["cfg2_prefill_only"]["launch_ms_avg"]
+            paths["cfg2_mixed_vs_parts"] = {"mixed_ms": round(launch_avg, 4), "max_of_parts_ms": round(max(td, tp), 4),
+                                            "sum_of_parts_ms": round(td + tp, 4)}
+        leg("cfg2_kv_append", lambda: append_figures(torch, hb, b, pools[0], 100, 10))
         del ring
         pools.clear()
         torch.cuda.empty_cache()
-        paths = {}
-        for which, name in ((3, "decode_heavy"), (4, "prefill_heavy")):
+
+        def big(which):
+            bb = synth.config(which, fill_pool=False)
+            if which == 4:
+                bb = bb.sub_batch(synth.PREFILL)
+            pp = device_pool(torch, bb, 1000 + which, copies=1 if which == 3 else 2)
             try:
-                paths[name] = path_figures(torch, hb, synth, which, 30, 5)
-            except Exception as e:  # the headline above stands on its own
-                paths[name] = {"error": repr(e)}
+                return path_figures(torch, hb, bb, pp, 30, 5)
+            finally:
+                del pp
+                torch.cuda.empty_cache()
+
+        leg("decode_heavy", lambda: big(3))
+        leg("prefill_heavy", lambda: big(4))
+
+        def short_context():
+            bb = synth.table1_short_context(seed=7, requests_per_task=64)
+            pp = [torch.from_numpy(bb.pool.view(np.int16)).cuda()]
+            out = path_figures(torch, hb, bb, pp, 100, 10)
+            st = hb.DeviceStep(bb, pool_dev=pp[0])
+            t0 = time.perf_counter()
+            for _ in range(50):
+                st.build(stream)
+                torch.cuda.synchronize()
+            out["desc_build_upload_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
+            return out
+
+        leg("table1_short_context", short_context)
         result["paths"] = paths
 
     print(json.dumps(result))

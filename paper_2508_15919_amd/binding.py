@@ -289,6 +289,13 @@ class DeviceStep:
             raise HfxError(rc, "hfx_mixed_paged_attention")
         return self.out
 
+    def append(self, k_new, v_new, stream=None):
+        """hfx_append_kv: the chunk tokens' K/V ([T, Hkv, D] device tensors) go into the step's pages."""
+        rc = self._lib.hfx_append_kv(ctypes.byref(self.shape), _ptr(k_new), _ptr(v_new), _ptr(self._pool),
+                                     _ptr(self.host_desc), _ptr(self.device_desc), self._stream_ptr(stream))
+        if rc != HFX_OK:
+            raise HfxError(rc, "hfx_append_kv")
+
     def out_bits(self) -> np.ndarray:
         self.torch.cuda.synchronize(self.device)
         return self.out.cpu().numpy().view(np.uint16)

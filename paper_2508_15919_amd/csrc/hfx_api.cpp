@@ -72,11 +72,18 @@ hfx_status hfx_version(int32_t* major, int32_t* minor) {
   return HFX_OK;
 }
 
+// One planner scratch per host thread: its vectors keep their capacity, so steady-state calls do
+// not touch the allocator (fresh pages for a megabyte of items cost more than planning them).
+static hfx::Plan& tls_plan() {
+  static thread_local hfx::Plan plan;
+  return plan;
+}
+
 hfx_status hfx_batch_desc_sizes(const hfx_shape* shape, int32_t num_requests, const int32_t* kind,
                                 const int32_t* q_len, const int32_t* ctx_len, size_t* host_desc_bytes,
                                 size_t* device_desc_bytes, size_t* device_workspace_bytes) {
   if (!host_desc_bytes || !device_desc_bytes || !device_workspace_bytes) return HFX_ERR_NULL;
-  hfx::Plan plan;
+  hfx::Plan& plan = tls_plan();
   hfx_status st = hfx::plan_step(shape, num_requests, kind, q_len, ctx_len, &plan);
   if (st != HFX_OK) return st;
   HfxHeader h;
@@ -90,7 +97,7 @@ hfx_status hfx_batch_desc_sizes(const hfx_shape* shape, int32_t num_requests, co
 hfx_status hfx_fill_batch_desc(const hfx_shape* shape, int32_t num_requests, const int32_t* kind,
                                const int32_t* q_len, const int32_t* ctx_len, const int32_t* bt_indptr,
                                const int32_t* bt_pages, void* host_desc, size_t host_desc_bytes) {
-  hfx::Plan plan;
+  hfx::Plan& plan = tls_plan();
   hfx_status st = hfx::plan_step(shape, num_requests, kind, q_len, ctx_len, &plan);
   if (st != HFX_OK) return st;
   return hfx::fill_blob(shape, plan, bt_indptr, bt_pages, host_desc, host_desc_bytes);

@@ -38,14 +38,15 @@ hfx_status check_shape(const hfx_shape* s) {
   return HFX_OK;
 }
 
-// visible (row, key) pairs of chunk rows [r0, r1) against keys [kb, ke); row i sees keys <= p+i
+// visible (row, key) pairs of chunk rows [r0, r1) against keys [kb, ke); row i sees keys <= p+i.
+// Rows below i_lo see nothing of the range, rows from i_hi on see all of it, the rows between
+// see p+i+1-kb keys (an arithmetic series).
 static int64_t pairs_in(int64_t p, int64_t r0, int64_t r1, int64_t kb, int64_t ke) {
-  int64_t n = 0;
-  for (int64_t i = r0; i < r1; ++i) {
-    int64_t hi = std::min<int64_t>(ke, p + i + 1);
-    if (hi > kb) n += hi - kb;
-  }
-  return n;
+  if (ke <= kb || r1 <= r0) return 0;
+  const int64_t i_lo = std::min(r1, std::max(r0, kb - p));
+  const int64_t i_hi = std::min(r1, std::max(i_lo, ke - p - 1));
+  const int64_t n = i_hi - i_lo;
+  return n * (p + 1 - kb) + (i_lo + i_hi - 1) * n / 2 + (r1 - i_hi) * (ke - kb);
 }
 
 static int32_t clamp_cost(double ns) {
@@ -96,6 +97,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   const double cap_prefill_ns = std::max(total_ns / (HFX_PLAN_WGS * kPrefillItemsPerWg), kMinItemNs);
 
   int64_t rows = 0;
+  std::vector<int32_t>& split_cost = P.split_cost;
   const int ngc = kv_heads_per_item(Hkv);
   const int hpw = q_heads_per_item(G);
   const int rows_wg = HFX_WAVE_ROWS * (4 / hpw);
@@ -133,6 +135,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
           it.ke = (int32_t)std::min<int64_t>(q.n_pages, (int64_t)(s + 1) * pages_per);
           int64_t toks = std::min<int64_t>(q.ctx_len, (int64_t)it.ke * HFX_PAGE) - (int64_t)it.kb * HFX_PAGE;
           it.cost = clamp_cost((double)toks * ns_per_token + 2000.0);
+          it.rq = q;
           P.items.push_back(it);
         }
         if (nsplit > 1) rows += (int64_t)nsplit * ngc * G;
@@ -150,6 +153,11 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
         int64_t tiles_per = (ntiles + nsplit - 1) / nsplit;
         tiles_per = std::max<int64_t>(tiles_per, kMinPrefillKeys / HFX_KEY_TILE);
         nsplit = (ntiles + tiles_per - 1) / tiles_per;
+        split_cost.resize((size_t)nsplit);
+        for (int64_t s = 0; s < nsplit; ++s) {
+          const int64_t kb = s * tiles_per * HFX_KEY_TILE, ke = std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
+          split_cost[(size_t)s] = clamp_cost(4.0 * D * hpw * (double)pairs_in(p, r0, r1, kb, ke) / kPrefillFlopsPerNs + 3000.0);
+        }
         for (int g = 0; g < Hkv; ++g)
           for (int hb = 0; hb < G / hpw; ++hb) {
             int group = -1;
@@ -171,7 +179,8 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
               it.nrows = rows_wg;
               it.kb = (int32_t)(s * tiles_per * HFX_KEY_TILE);
               it.ke = (int32_t)std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
-              it.cost = clamp_cost(4.0 * D * hpw * (double)pairs_in(p, r0, r1, it.kb, it.ke) / kPrefillFlopsPerNs + 3000.0);
+              it.cost = split_cost[(size_t)s];
+              it.rq = q;
               P.items.push_back(it);
             }
             if (nsplit > 1) rows += nsplit * 4 * HFX_WAVE_ROWS;
@@ -181,8 +190,37 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     if (rows > 0x7fffffff / 2 || P.items.size() > 0x3fffffffu) return HFX_ERR_LEN;
   }
   P.n_partial_rows = (int32_t)rows;
-  std::stable_sort(P.items.begin(), P.items.end(),
-                   [](const HfxItem& a, const HfxItem& b) { return a.cost > b.cost; });
+  // queue order: descending cost, ties in creation order: a stable radix sort (11-bit digits) of
+  // (inverted cost, index) keys, then one permutation of the 80-byte items.
+  {
+    const size_t n = P.items.size();
+    std::vector<uint64_t>& key = P.sort_keys;
+    key.resize(2 * n);
+    uint64_t* a = key.data();
+    uint64_t* b = a + n;
+    uint32_t top = 0;
+    for (size_t i = 0; i < n; ++i) {
+      const uint32_t inv = 0x7fffffffu - (uint32_t)P.items[i].cost;
+      a[i] = ((uint64_t)inv << 32) | (uint64_t)i;
+      top |= inv;
+    }
+    for (int shift = 0; shift < 31 && (top >> shift) != 0; shift += 11) {
+      uint32_t count[2048] = {0};
+      for (size_t i = 0; i < n; ++i) count[(a[i] >> (32 + shift)) & 2047u]++;
+      uint32_t sum = 0;
+      for (int d = 0; d < 2048; ++d) {
+        const uint32_t c = count[d];
+        count[d] = sum;
+        sum += c;
+      }
+      for (size_t i = 0; i < n; ++i) b[count[(a[i] >> (32 + shift)) & 2047u]++] = a[i];
+      std::swap(a, b);
+    }
+    std::vector<HfxItem>& sorted = P.sort_tmp;
+    sorted.resize(n);
+    for (size_t i = 0; i < n; ++i) sorted[i] = P.items[(size_t)(a[i] & 0xffffffffu)];
+    P.items.swap(sorted);
+  }
   // merge work units: groups with many splits get 8 threads per (row, column) and one row per
   // workgroup, groups with few splits one thread per (row, column) and 8 rows per workgroup
   P.units.clear();
@@ -193,7 +231,6 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       P.units.push_back(u);
     }
   }
-  for (HfxItem& it : P.items) it.rq = P.reqs[(size_t)it.req];
   P.n_decode_items = P.n_prefill_items = 0;
   for (const HfxItem& it : P.items) (it.type == HFX_ITEM_DECODE ? P.n_decode_items : P.n_prefill_items)++;
   return HFX_OK;
@@ -261,15 +298,21 @@ hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, 
       if (src[i] < 0 || src[i] >= shape->num_pages) return HFX_ERR_PAGE_ID;
   }
   char* base = (char*)host_desc;
-  std::memset(base, 0, (size_t)h.total_bytes);
-  std::memcpy(base, &h, sizeof h);
-  std::memcpy(base + h.off_req, P.reqs.data(), sizeof(HfxReq) * P.reqs.size());
+  // every byte of the blob is written: sections by copy, the padding between them with zeros
+  auto put = [base](uint64_t off, const void* src, uint64_t bytes, uint64_t next_off) {
+    if (bytes) std::memcpy(base + off, src, (size_t)bytes);
+    std::memset(base + off + bytes, 0, (size_t)(next_off - off - bytes));
+  };
+  put(0, &h, sizeof h, h.off_ctrl);
+  put(h.off_ctrl, nullptr, 0, h.off_req);
+  put(h.off_req, P.reqs.data(), sizeof(HfxReq) * P.reqs.size(), h.off_bt);
   int32_t* bt = (int32_t*)(base + h.off_bt);
   for (int r = 0; r < R; ++r)
     std::memcpy(bt + P.reqs[(size_t)r].bt_start, bt_pages + bt_indptr[r], 4ull * (size_t)P.reqs[(size_t)r].n_pages);
-  std::memcpy(base + h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size());
-  if (!P.groups.empty()) std::memcpy(base + h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size());
-  if (!P.units.empty()) std::memcpy(base + h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size());
+  put(h.off_bt + 4ull * (uint64_t)P.n_bt, nullptr, 0, h.off_items);
+  put(h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size(), h.off_groups);
+  put(h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size(), h.off_units);
+  put(h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size(), h.total_bytes);
   return HFX_OK;
 }
 

@@ -15,6 +15,10 @@ struct Plan {
   std::vector<HfxGroup> groups;
   std::vector<HfxUnit> units;
   int32_t total_q = 0, n_bt = 0, n_partial_rows = 0, n_decode_items = 0, n_prefill_items = 0;
+  // scratch of plan_step, kept so that a reused Plan allocates nothing once it has grown
+  std::vector<uint64_t> sort_keys;
+  std::vector<HfxItem> sort_tmp;
+  std::vector<int32_t> split_cost;
 };
 
 hfx_status check_shape(const hfx_shape* shape);

@@ -90,8 +90,14 @@ def check_coverage(b, d):
                 assert it["h0"] // G == (it["h0"] + it["hn"] - 1) // G, "an item stays inside one kv group"
                 r1 = min(ql, it["row0"] + it["nrows"])
                 cover[it["h0"]:it["h0"] + it["hn"], it["row0"]:r1, it["kb"]:it["ke"]] += 1
+                # modelled cost: 4*D flops per visible pair per q-head at 2000 flops/ns, plus a fixed 3000 ns
+                rows_i = np.arange(it["row0"], r1)
+                pairs = int(np.clip(np.minimum(it["ke"], p + rows_i + 1) - it["kb"], 0, None).sum())
+                assert it["cost"] == int(4.0 * b.head_dim * it["hn"] * pairs / 2000.0 + 3000.0)
             visible = (np.arange(c)[None, :] <= (p + np.arange(ql))[:, None])
             assert np.all(cover[:, visible] == 1), "every visible pair exactly once"
+        for f in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages"):
+            assert np.all(mine["rq_" + f] == reqs[f][r]), "an item carries a copy of its request record"
         for it in mine:
             if it["group"] >= 0:
                 g = groups[it["group"]]
