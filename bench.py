@@ -277,6 +277,25 @@ def main() -> int:
             return out
 
         leg("table1_short_context", short_context)
+
+        def latency_model():
+            # E_p = a + b*n_token (the linear model of the paper's token-budget formula), fitted to this
+            # kernel on prompt batches with Table-1 lengths; E_d = the headline step's decode part
+            ns, ts = [], []
+            for rpt in (4, 8, 16, 32, 64, 128):
+                bb = synth.table1_short_context(seed=11, requests_per_task=rpt).sub_batch(synth.PREFILL)
+                pp = [torch.from_numpy(bb.pool.view(np.int16)).cuda()]
+                f = path_figures(torch, hb, bb, pp, 50, 5)
+                ns.append(bb.total_q)
+                ts.append(f["launch_ms_avg"] * 1e-3)
+            e_d = paths.get("cfg2_decode_only", {}).get("launch_ms_avg", 0.11) * 1e-3
+            model, r2 = hb.hfx_fit_latency_model(ns, ts, e_d)
+            ttft, tpot = 100 * e_d, 4 * e_d          # an example SLO pair in units of this layer's decode time
+            return {"n_token": ns, "seconds": [round(t, 7) for t in ts], "a_s": model.a, "b_s_per_token": model.b,
+                    "r_squared": round(r2, 5), "e_d_s": e_d,
+                    "example": {"ttft_s": ttft, "tpot_s": tpot, "token_budget": hb.hfx_token_budget(ttft, tpot, model)}}
+
+        leg("latency_model", latency_model)
         result["paths"] = paths
 
     print(json.dumps(result))

@@ -14,8 +14,9 @@
  * grouped-query head sharing, defined precisely at hfx_mixed_paged_attention.
  *
  * C ABI only: plain pointers and sizes.  Every pointer argument is tagged
- * [host] or [device] below.  The library never allocates or frees memory that
- * outlives a call and never synchronises a stream.  No function throws or
+ * [host] or [device] below.  The library never allocates or frees device
+ * memory and never synchronises a stream; the only memory it keeps between
+ * calls is a host-side planner scratch per calling thread.  No function throws or
  * aborts; every failure is a negative hfx_status and, when it is a validation
  * failure, nothing has been enqueued on the stream.
  */
@@ -42,7 +43,8 @@ enum {
   HFX_ERR_BUFSIZE = -7,  /* a caller-provided buffer is too small                       */
   HFX_ERR_DEVICE = -8,   /* the HIP runtime reported an error                           */
   HFX_ERR_DESC = -9,     /* the descriptor blob is not one this library version wrote   */
-  HFX_ERR_ALIGN = -10    /* a device pointer is not 16-byte aligned                     */
+  HFX_ERR_ALIGN = -10,   /* a device pointer is not 16-byte aligned                     */
+  HFX_ERR_MODEL = -11    /* latency model or SLO values are not usable (see hfx_token_budget) */
 };
 
 /* Request kinds of a scheduled step (Section 3.3.1: in-flight decoding requests
@@ -150,7 +152,9 @@ hfx_status hfx_fill_batch_desc(const hfx_shape* shape, int32_t num_requests,
                                size_t host_desc_bytes);
 
 /*
- * Executes the attention of one scheduled step in a single persistent launch.
+ * Executes the attention of one scheduled step: one persistent launch drains
+ * the step's work items, and, when the plan split some of them, one small
+ * launch behind it on the same stream merges the partial results.
  *
  * With T = sum of q_len, requests packed in order (request r owns query rows
  * [sum_{s<r} q_len[s], +q_len[r])):
@@ -215,6 +219,89 @@ hfx_status hfx_gather_kv(const hfx_shape* shape, const void* kv_pool,
 hfx_status hfx_append_kv(const hfx_shape* shape, const void* k_new, const void* v_new,
                          void* kv_pool, const void* host_desc, const void* device_desc,
                          void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Step composition (host only): the closed forms of Section 3.3.1 that decide how many
+ * prompt tokens a step may carry, and a one-instance form of the dispatching steps that
+ * turns a waiting queue into the arrays hfx_build_batch_desc takes.
+ * All times are in seconds.  Nothing here touches a device.
+ * ---------------------------------------------------------------------------------------- */
+
+/* Latency model of one instance (Section 3.3.1): a prefill batch of n prompt tokens takes
+ * E_p = a + b*n (the linear model the paper adopts), a decode iteration of the current
+ * running batch takes the constant E_d. */
+typedef struct {
+  double a;    /* fixed cost of a prefill batch, >= 0   */
+  double b;    /* cost per prompt token, > 0            */
+  double e_d;  /* duration of one decode iteration, >= 0 */
+} hfx_latency_model;
+
+/*
+ * Token budget, Eq. (3): the largest integer n with 2*E_p + k*E_d <= TTFT, where
+ * E_p = a + b*n and k = E_p / (TPOT - E_d), i.e.
+ *   n <= (TPOT - E_d)*TTFT / ((2*TPOT - E_d)*b) - a/b.
+ * Writes floor of the bound, clamped to [0, INT64_MAX/2], to *n_token.  When the decode
+ * iteration leaves no slack (E_d >= TPOT) the budget is 0: no prefill can be absorbed.
+ * Errors: HFX_ERR_NULL; HFX_ERR_MODEL if ttft or tpot <= 0, b <= 0, a < 0, e_d < 0, or any
+ * value is not finite.
+ */
+hfx_status hfx_token_budget(double ttft, double tpot, const hfx_latency_model* model,
+                            int64_t* n_token);
+
+/*
+ * Maturity time (Section 3.3.1): after a prefill batch of duration e_p, k = e_p/(TPOT - E_d)
+ * decode iterations rebuild the slack the batch consumed (k is kept real-valued, as in the
+ * paper's formula); the instance can admit again at  maturity = e_p + k*E_d.
+ * Writes k and maturity (either pointer may be NULL).  With E_d >= TPOT there is no slack to
+ * rebuild: returns HFX_ERR_MODEL.  Other errors as hfx_token_budget.
+ */
+hfx_status hfx_maturity_time(double e_p, double tpot, double e_d, double* k, double* maturity);
+
+/*
+ * Least-squares fit of E_p = a + b*n to measured prefill batches (n_token[i], seconds[i]),
+ * i < count, count >= 2 with at least two distinct n_token.  Also writes the coefficient of
+ * determination R^2 (may be NULL): the check of the paper's claim that the quadratic term
+ * is negligible.  e_d of *model is left untouched.  a is clamped at 0.
+ * Errors: HFX_ERR_NULL, HFX_ERR_MODEL (degenerate input or b <= 0).
+ */
+hfx_status hfx_fit_latency_model(int32_t count, const int64_t* n_token, const double* seconds,
+                                 hfx_latency_model* model, double* r_squared);
+
+/*
+ * One dispatching decision for one instance (the four steps of Section 3.3.1 with a single
+ * instance, so step 1 is trivial): compute the token budget from the strictest TTFT / TPOT
+ * given, scan the waiting queue in ascending `urgency` (ties: queue order) and admit every
+ * request whose prompt still fits in what is left of the budget, then predict E_p, k and the
+ * new maturity time of the instance.
+ *
+ *   n_running, running_ctx   [host] in-flight decode requests and the KV tokens each has now
+ *   n_waiting, prompt_len    [host] waiting requests and their prompt lengths (>= 1)
+ *   urgency                  [host] smaller = more urgent (e.g. TTFT deadline); NULL = queue order
+ *   mixed                    0: the step is the admitted prompts alone (the prefill batch that
+ *                               pre-empts decoding, as in the paper's colocated mode);
+ *                            1: the running requests' next decode tokens ride in the same step
+ *   admitted                 [host] out, n_waiting flags (1 = dispatched in this step)
+ *   kind, q_len, ctx_len     [host] out, capacity n_running + n_waiting each: the step in the
+ *                            form hfx_batch_desc_sizes / hfx_build_batch_desc take.  Decodes
+ *                            first (q 1, ctx running_ctx+1), then admitted prompts in scan
+ *                            order (q = ctx = prompt_len)
+ *   n_step                   [host] out, number of requests in the step (0 = nothing to run)
+ *   decision                 [host] out, may be NULL
+ * Errors: HFX_ERR_NULL, HFX_ERR_LEN (a length < 1), HFX_ERR_MODEL.
+ */
+typedef struct {
+  int64_t budget;       /* Eq. (3)                                  */
+  int64_t n_token;      /* prompt tokens admitted (<= budget)       */
+  double e_p;           /* a + b*n_token (0 if nothing admitted)    */
+  double k;             /* decode iterations until maturity         */
+  double maturity;      /* e_p + k*E_d                              */
+} hfx_decision;
+
+hfx_status hfx_compose_step(double ttft, double tpot, const hfx_latency_model* model,
+                            int32_t n_running, const int32_t* running_ctx, int32_t n_waiting,
+                            const int32_t* prompt_len, const double* urgency, int32_t mixed,
+                            int32_t* admitted, int32_t* kind, int32_t* q_len, int32_t* ctx_len,
+                            int32_t* n_step, hfx_decision* decision);
 
 #ifdef __cplusplus
 }

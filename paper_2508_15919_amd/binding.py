@@ -17,16 +17,27 @@ LIB_PATH = os.path.join(_HERE, "libhfxattn.so")
 HFX_OK = 0
 HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_KIND, HFX_ERR_LEN, HFX_ERR_PAGES = -1, -2, -3, -4, -5
 HFX_ERR_PAGE_ID, HFX_ERR_BUFSIZE, HFX_ERR_DEVICE, HFX_ERR_DESC, HFX_ERR_ALIGN = -6, -7, -8, -9, -10
+HFX_ERR_MODEL = -11
 HFX_DECODE, HFX_PREFILL = 0, 1
 
 EXPORTS = ["hfx_status_string", "hfx_version", "hfx_batch_desc_sizes", "hfx_build_batch_desc",
-           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv", "hfx_append_kv"]
+           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv", "hfx_append_kv",
+           "hfx_token_budget", "hfx_maturity_time", "hfx_fit_latency_model", "hfx_compose_step"]
 
 
 class hfx_shape(ctypes.Structure):
     _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("num_pages", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class hfx_latency_model(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_double), ("b", ctypes.c_double), ("e_d", ctypes.c_double)]
+
+
+class hfx_decision(ctypes.Structure):
+    _fields_ = [("budget", ctypes.c_int64), ("n_token", ctypes.c_int64), ("e_p", ctypes.c_double),
+                ("k", ctypes.c_double), ("maturity", ctypes.c_double)]
 
 
 class HfxError(RuntimeError):
@@ -67,6 +78,18 @@ def load() -> ctypes.CDLL:
         lib.hfx_gather_kv.restype = ctypes.c_int32
         lib.hfx_append_kv.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         lib.hfx_append_kv.restype = ctypes.c_int32
+        dbl, dblp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+        i64p, lmp = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(hfx_latency_model)
+        lib.hfx_token_budget.argtypes = [dbl, dbl, lmp, i64p]
+        lib.hfx_token_budget.restype = ctypes.c_int32
+        lib.hfx_maturity_time.argtypes = [dbl, dbl, dbl, dblp, dblp]
+        lib.hfx_maturity_time.restype = ctypes.c_int32
+        lib.hfx_fit_latency_model.argtypes = [ctypes.c_int32, i64p, dblp, lmp, dblp]
+        lib.hfx_fit_latency_model.restype = ctypes.c_int32
+        lib.hfx_compose_step.argtypes = [dbl, dbl, lmp, ctypes.c_int32, i32p, ctypes.c_int32, i32p, dblp,
+                                         ctypes.c_int32, i32p, i32p, i32p, i32p, i32p,
+                                         ctypes.POINTER(hfx_decision)]
+        lib.hfx_compose_step.restype = ctypes.c_int32
         _lib = lib
     return _lib
 
@@ -182,6 +205,60 @@ def hfx_append_kv(shape: hfx_shape, k_new, v_new, kv_pool, host_desc, device_des
                               _ptr(device_desc), _stream(stream))
     if rc != HFX_OK:
         raise HfxError(rc, "hfx_append_kv")
+
+
+def hfx_token_budget(ttft: float, tpot: float, model: hfx_latency_model) -> int:
+    n = ctypes.c_int64(-1)
+    rc = load().hfx_token_budget(ttft, tpot, ctypes.byref(model), ctypes.byref(n))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_token_budget")
+    return int(n.value)
+
+
+def hfx_maturity_time(e_p: float, tpot: float, e_d: float):
+    k, m = ctypes.c_double(), ctypes.c_double()
+    rc = load().hfx_maturity_time(e_p, tpot, e_d, ctypes.byref(k), ctypes.byref(m))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_maturity_time")
+    return k.value, m.value
+
+
+def hfx_fit_latency_model(n_token, seconds, e_d: float = 0.0):
+    """Returns (model, r_squared)."""
+    n = np.ascontiguousarray(n_token, dtype=np.int64)
+    t = np.ascontiguousarray(seconds, dtype=np.float64)
+    assert n.shape == t.shape and n.ndim == 1
+    model, r2 = hfx_latency_model(0.0, 0.0, e_d), ctypes.c_double()
+    rc = load().hfx_fit_latency_model(len(n), n.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                      t.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.byref(model),
+                                      ctypes.byref(r2))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_fit_latency_model")
+    return model, r2.value
+
+
+def hfx_compose_step(ttft: float, tpot: float, model: hfx_latency_model, running_ctx, prompt_len, urgency=None,
+                     mixed: bool = False):
+    """Returns (admitted flags, kind, q_len, ctx_len, hfx_decision)."""
+    rc_arr, prc = _i32(np.asarray(running_ctx, dtype=np.int32))
+    pl_arr, ppl = _i32(np.asarray(prompt_len, dtype=np.int32))
+    urg = purg = None
+    if urgency is not None:
+        urg = np.ascontiguousarray(urgency, dtype=np.float64)
+        purg = urg.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    cap = max(1, len(rc_arr) + len(pl_arr))
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    adm = np.zeros(max(1, len(pl_arr)), np.int32)
+    kind, ql, cl = (np.zeros(cap, np.int32) for _ in range(3))
+    n_step, dec = ctypes.c_int32(), hfx_decision()
+    rc = load().hfx_compose_step(ttft, tpot, ctypes.byref(model), len(rc_arr), prc, len(pl_arr), ppl, purg,
+                                 int(bool(mixed)), adm.ctypes.data_as(i32p), kind.ctypes.data_as(i32p),
+                                 ql.ctypes.data_as(i32p), cl.ctypes.data_as(i32p), ctypes.byref(n_step),
+                                 ctypes.byref(dec))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_compose_step")
+    n = n_step.value
+    return adm[:len(pl_arr)], kind[:n], ql[:n], cl[:n], dec
 
 
 # ------------------------------------------------------------------------------------------

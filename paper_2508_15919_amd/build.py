@@ -8,10 +8,11 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhfxattn.so")
-SOURCES = ["hfx_kernels.hip", "hfx_api.cpp", "hfx_plan.cpp"]
+SOURCES = ["hfx_kernels.hip", "hfx_api.cpp", "hfx_plan.cpp", "hfx_sched.cpp"]
 # -fno-honor-nans: no floating-point operation in the kernels is ever fed a NaN (possibly-NaN scores
 # are masked through integer selects first), and without it every max carries a canonicalising twin.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-fno-honor-nans",
+# Device code only: the host side validates its floating-point arguments with NaN tests.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Xarch_device", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

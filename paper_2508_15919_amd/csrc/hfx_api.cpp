@@ -62,6 +62,7 @@ const char* hfx_status_string(hfx_status s) {
     case HFX_ERR_DEVICE: return "HIP runtime error";
     case HFX_ERR_DESC: return "not a batch descriptor of this library version";
     case HFX_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case HFX_ERR_MODEL: return "latency model or SLO values not usable";
     default: return "unknown status";
   }
 }
