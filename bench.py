@@ -107,6 +107,35 @@ def append_figures(torch, hb, batch, pool, iters, warmup):
             "achieved_GBs": round(byt / avg / 1e6, 1)}
 
 
+def copy_figures(torch, hb, batch, src, dst, iters, warmup):
+    """hfx_copy_pages of every page the step's requests hold, from one pool into another."""
+    ids = np_unique_pages(batch)
+    shape = hb.make_shape(batch.num_q_heads, batch.num_kv_heads, batch.head_dim, batch.num_pages, 0.0)
+    host_stage = torch.empty(8 * len(ids), dtype=torch.uint8, pin_memory=True)
+    dev_stage = torch.empty(8 * len(ids), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        hb.hfx_copy_pages(shape, src, dst, batch.num_pages, ids, ids, host_stage, dev_stage, stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, c in evs:
+        a.record(stream)
+        hb.hfx_copy_pages(shape, src, dst, batch.num_pages, ids, ids, host_stage, dev_stage, stream)
+        c.record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(c) for a, c in evs)
+    avg = sum(ms) / len(ms)
+    page_bytes = batch.num_kv_heads * 2 * 16 * batch.head_dim * 2
+    byt = 2 * len(ids) * page_bytes          # every page read once and written once
+    return {"workload": batch.name + "/page-copy", "pages": int(len(ids)), "launch_ms_avg": round(avg, 5),
+            "launch_ms_min": round(ms[0], 5), "bound": "hbm", "algorithmic_bytes": byt,
+            "achieved_GBs": round(byt / avg / 1e6, 1), "frac_of_hbm_peak": round(byt / avg / 1e6 / HBM_PEAK_GBS, 4)}
+
+
+def np_unique_pages(batch):
+    import numpy as np
+    return np.unique(batch.bt_pages).astype(np.int32)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +275,8 @@ def main() -> int:
             paths["cfg2_mixed_vs_parts"] = {"mixed_ms": round(launch_avg, 4), "max_of_parts_ms": round(max(td, tp), 4),
                                             "sum_of_parts_ms": round(td + tp, 4)}
         leg("cfg2_kv_append", lambda: append_figures(torch, hb, b, pools[0], 100, 10))
+        if len(pools) > 1:      # the pools are copies of each other, so the move leaves their contents as they are
+            leg("cfg2_page_copy", lambda: copy_figures(torch, hb, b, pools[0], pools[1], 50, 5))
         del ring
         pools.clear()
         torch.cuda.empty_cache()

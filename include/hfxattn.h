@@ -220,6 +220,33 @@ hfx_status hfx_append_kv(const hfx_shape* shape, const void* k_new, const void* 
                          void* kv_pool, const void* host_desc, const void* device_desc,
                          void* stream);
 
+/*
+ * Copies whole KV pages between two pools of the same geometry (Hkv, D, page size), or inside
+ * one pool: page src_ids[i] of src_pool becomes page dst_ids[i] of dst_pool, bit for bit.
+ * This is the device half of handing a request's KV blocks from the instance that prefilled
+ * it to the instance that decodes it (Section 3.3.1, disaggregated mode; Section 3.4), with
+ * both pools on this GPU; the block table of the receiving side is dst_ids.
+ *
+ *   shape          geometry; shape->num_pages is the size of src_pool
+ *   src_pool       [device] source pool, layout as at the top of this file
+ *   dst_pool       [device] destination pool with dst_num_pages pages (may equal src_pool)
+ *   src_ids, dst_ids [host] num_pairs page ids each.  dst ids are pairwise distinct; when the
+ *                  pools are the same buffer no dst id is also a src id (HFX_ERR_PAGES)
+ *   host_stage     [host]   >= 8*num_pairs bytes, written here and read by the upload: leave
+ *                  it alone until the stream has passed this call (pinned memory keeps the
+ *                  call asynchronous)
+ *   device_stage   [device] >= 8*num_pairs bytes, 16-byte aligned
+ *   stage_bytes    size of each staging buffer
+ *
+ * Asynchronous on `stream`; allocates no device memory.  num_pairs == 0 is a no-op.
+ * Errors: HFX_ERR_NULL, HFX_ERR_SHAPE, HFX_ERR_PAGE_ID, HFX_ERR_PAGES, HFX_ERR_BUFSIZE,
+ * HFX_ERR_ALIGN, HFX_ERR_DEVICE; on a validation error nothing is enqueued.
+ */
+hfx_status hfx_copy_pages(const hfx_shape* shape, const void* src_pool, void* dst_pool,
+                          int32_t dst_num_pages, int32_t num_pairs, const int32_t* src_ids,
+                          const int32_t* dst_ids, void* host_stage, void* device_stage,
+                          size_t stage_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Step composition (host only): the closed forms of Section 3.3.1 that decide how many
  * prompt tokens a step may carry, and a one-instance form of the dispatching steps that

@@ -271,3 +271,19 @@ int hfx_oracle_append_kv(int Hkv, int D, long num_pages, int R, const int32_t* q
   }
   return 0;
 }
+
+/* Page copy between two pools of one geometry: page src_ids[i] of src becomes page dst_ids[i] of
+ * dst, element by element (the KV blocks of a request handed from a prefill instance to a decode
+ * instance, Section 3.3.1 disaggregated mode / Section 3.4).  A page is Hkv*2*16*D elements. */
+int hfx_oracle_copy_pages(int Hkv, int D, long src_num_pages, long dst_num_pages, long n,
+                          const int32_t* src_ids, const int32_t* dst_ids, const uint16_t* src,
+                          uint16_t* dst) {
+  if (D <= 0 || Hkv <= 0) return -2;
+  const size_t page_elems = (size_t)Hkv * 2 * ORC_PAGE * (size_t)D;
+  for (long i = 0; i < n; ++i) {
+    if (src_ids[i] < 0 || src_ids[i] >= src_num_pages || dst_ids[i] < 0 || dst_ids[i] >= dst_num_pages) return -6;
+    for (size_t e = 0; e < page_elems; ++e)
+      dst[(size_t)dst_ids[i] * page_elems + e] = src[(size_t)src_ids[i] * page_elems + e];
+  }
+  return 0;
+}

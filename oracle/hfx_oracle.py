@@ -47,6 +47,9 @@ def _load():
         lib.hfx_oracle_append_kv.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_int, i32p, i32p,
                                              i32p, i32p, u16p, u16p, u16p]
         lib.hfx_oracle_append_kv.restype = ctypes.c_int
+        lib.hfx_oracle_copy_pages.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_long,
+                                              i32p, i32p, u16p, u16p]
+        lib.hfx_oracle_copy_pages.restype = ctypes.c_int
         lib.hfx_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -146,5 +149,20 @@ def append_kv(Hkv, D, num_pages, q_len, ctx_len, bt_indptr, bt_pages, k_new, v_n
     assert pool.dtype == np.uint16 and pool.flags.c_contiguous
     rc = _load().hfx_oracle_append_kv(int(Hkv), int(D), int(num_pages), len(ql), pql, pcl, pbi, pbp, pkn, pvn,
                                       pool.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the inputs (code {rc})")
+
+
+def copy_pages(Hkv, D, src_ids, dst_ids, src_pool, dst_pool):
+    """dst_pool[dst_ids[i]] = src_pool[src_ids[i]] (whole pages, in place on dst_pool; both contiguous uint16
+    arrays whose leading axis is the page)."""
+    si, psi = _i32(src_ids)
+    di, pdi = _i32(dst_ids)
+    assert len(si) == len(di)
+    assert src_pool.dtype == np.uint16 and src_pool.flags.c_contiguous
+    assert dst_pool.dtype == np.uint16 and dst_pool.flags.c_contiguous
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    rc = _load().hfx_oracle_copy_pages(int(Hkv), int(D), src_pool.shape[0], dst_pool.shape[0], len(si), psi, pdi,
+                                       src_pool.ctypes.data_as(u16p), dst_pool.ctypes.data_as(u16p))
     if rc != 0:
         raise ValueError(f"oracle rejected the inputs (code {rc})")

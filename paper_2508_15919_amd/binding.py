@@ -22,7 +22,7 @@ HFX_DECODE, HFX_PREFILL = 0, 1
 
 EXPORTS = ["hfx_status_string", "hfx_version", "hfx_batch_desc_sizes", "hfx_build_batch_desc",
            "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv", "hfx_append_kv",
-           "hfx_token_budget", "hfx_maturity_time", "hfx_fit_latency_model", "hfx_compose_step"]
+           "hfx_copy_pages", "hfx_token_budget", "hfx_maturity_time", "hfx_fit_latency_model", "hfx_compose_step"]
 
 
 class hfx_shape(ctypes.Structure):
@@ -78,6 +78,9 @@ def load() -> ctypes.CDLL:
         lib.hfx_gather_kv.restype = ctypes.c_int32
         lib.hfx_append_kv.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         lib.hfx_append_kv.restype = ctypes.c_int32
+        lib.hfx_copy_pages.argtypes = [shp, vp, vp, ctypes.c_int32, ctypes.c_int32, i32p, i32p, vp, vp,
+                                       ctypes.c_size_t, vp]
+        lib.hfx_copy_pages.restype = ctypes.c_int32
         dbl, dblp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
         i64p, lmp = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(hfx_latency_model)
         lib.hfx_token_budget.argtypes = [dbl, dbl, lmp, i64p]
@@ -205,6 +208,19 @@ def hfx_append_kv(shape: hfx_shape, k_new, v_new, kv_pool, host_desc, device_des
                               _ptr(device_desc), _stream(stream))
     if rc != HFX_OK:
         raise HfxError(rc, "hfx_append_kv")
+
+
+def hfx_copy_pages(shape: hfx_shape, src_pool, dst_pool, dst_num_pages: int, src_ids, dst_ids, host_stage,
+                   device_stage, stream=None, stage_bytes=None) -> None:
+    s_arr, ps = _i32(np.asarray(src_ids, dtype=np.int32))
+    d_arr, pd = _i32(np.asarray(dst_ids, dtype=np.int32))
+    assert len(s_arr) == len(d_arr)
+    rc = load().hfx_copy_pages(ctypes.byref(shape), _ptr(src_pool), _ptr(dst_pool), int(dst_num_pages), len(s_arr),
+                               ps, pd, _ptr(host_stage), _ptr(device_stage),
+                               min(_nbytes(host_stage), _nbytes(device_stage)) if stage_bytes is None
+                               else int(stage_bytes), _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_copy_pages")
 
 
 def hfx_token_budget(ttft: float, tpot: float, model: hfx_latency_model) -> int:

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
+#include <vector>
 
 #include "../../include/hfxattn.h"
 #include "hfx_desc.h"
@@ -170,6 +171,42 @@ hfx_status hfx_append_kv(const hfx_shape* shape, const void* k_new, const void* 
   const long pieces = (long)h.total_q * h.num_kv_heads * (h.head_dim / 8);
   if (hfx::launch_append_kv(device_desc, k_new, v_new, kv_pool, pieces, static_cast<hipStream_t>(stream)) !=
       hipSuccess)
+    return HFX_ERR_DEVICE;
+  return HFX_OK;
+}
+
+hfx_status hfx_copy_pages(const hfx_shape* shape, const void* src_pool, void* dst_pool, int32_t dst_num_pages,
+                          int32_t num_pairs, const int32_t* src_ids, const int32_t* dst_ids, void* host_stage,
+                          void* device_stage, size_t stage_bytes, void* stream) {
+  hfx_status st = hfx::check_shape(shape);
+  if (st != HFX_OK) return st;
+  if (num_pairs < 0 || dst_num_pages < 1) return HFX_ERR_SHAPE;
+  if (num_pairs == 0) return HFX_OK;
+  if (!src_pool || !dst_pool || !src_ids || !dst_ids || !host_stage || !device_stage) return HFX_ERR_NULL;
+  if (stage_bytes < 8ull * (size_t)num_pairs) return HFX_ERR_BUFSIZE;
+  if (!aligned16(src_pool) || !aligned16(dst_pool) || !aligned16(device_stage)) return HFX_ERR_ALIGN;
+  // a destination page is written once; inside one pool it is not read either
+  static thread_local std::vector<uint8_t> mark;
+  mark.assign((size_t)dst_num_pages, 0);
+  for (int i = 0; i < num_pairs; ++i) {
+    if (src_ids[i] < 0 || src_ids[i] >= shape->num_pages || dst_ids[i] < 0 || dst_ids[i] >= dst_num_pages)
+      return HFX_ERR_PAGE_ID;
+    if (mark[(size_t)dst_ids[i]]) return HFX_ERR_PAGES;
+    mark[(size_t)dst_ids[i]] = 1;
+  }
+  if (src_pool == dst_pool)
+    for (int i = 0; i < num_pairs; ++i)
+      if (src_ids[i] < dst_num_pages && mark[(size_t)src_ids[i]]) return HFX_ERR_PAGES;
+  int32_t* stage = static_cast<int32_t*>(host_stage);
+  for (int i = 0; i < num_pairs; ++i) {
+    stage[2 * i] = src_ids[i];
+    stage[2 * i + 1] = dst_ids[i];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(device_stage, host_stage, 8ull * (size_t)num_pairs, hipMemcpyHostToDevice, s) != hipSuccess)
+    return HFX_ERR_DEVICE;
+  const int units_per_page = shape->num_kv_heads * 2 * HFX_PAGE * shape->head_dim * 2 / 16;
+  if (hfx::launch_copy_pages(device_stage, num_pairs, units_per_page, src_pool, dst_pool, s) != hipSuccess)
     return HFX_ERR_DEVICE;
   return HFX_OK;
 }

@@ -732,6 +732,36 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Page copy: pool pages named by (src, dst) id pairs move between two pools of the same
+// geometry (or inside one).  The device half of handing a request's KV blocks from the
+// instance that prefilled it to the instance that decodes it (HFX Section 3.3.1,
+// disaggregated mode; Section 3.4).  16-byte units; a workgroup moves 16 KB with all of its
+// loads in flight before the first store.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_pages_kernel(const int2* __restrict__ pairs, long n_units,
+                                                         int units_per_page, const u32x4* __restrict__ src,
+                                                         u32x4* __restrict__ dst) {
+  const long base = (long)blockIdx.x * 1024 + threadIdx.x;
+  u32x4 v[4];
+  long to[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const long u = base + 256 * j;
+    to[j] = -1;
+    if (u < n_units) {
+      const long pr = u / units_per_page;
+      const int off = (int)(u - pr * units_per_page);
+      const int2 id = pairs[pr];
+      v[j] = __builtin_nontemporal_load(src + (long)id.x * units_per_page + off);
+      to[j] = (long)id.y * units_per_page + off;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (to[j] >= 0) __builtin_nontemporal_store(v[j], dst + to[j]);
+}
+
 // Page gather hook: one thread per (token, kv-head, dimension); a pure 2-byte copy through the
 // same request record and block table the attention kernel walks.
 __global__ void gather_kv_kernel(const char* desc, const uint16_t* pool, int request, uint16_t* k_out,
@@ -814,6 +844,18 @@ hipError_t launch_mixed_attention(int head_dim, int grid, int n_units, unsigned 
     else
       hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_pages(const void* pairs, long n_pairs, int units_per_page, const void* src, void* dst,
+                             hipStream_t stream) {
+  const long n_units = n_pairs * units_per_page;
+  if (n_units == 0) return hipSuccess;
+  const long blocks = (n_units + 1023) / 1024;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(copy_pages_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     static_cast<const int2*>(pairs), n_units, units_per_page, static_cast<const u32x4*>(src),
+                     static_cast<u32x4*>(dst));
   return hipGetLastError();
 }
 

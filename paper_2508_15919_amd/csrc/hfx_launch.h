@@ -13,4 +13,7 @@ hipError_t launch_gather_kv(const void* desc, const void* pool, int request, lon
 hipError_t launch_append_kv(const void* desc, const void* k_new, const void* v_new, void* pool, long pieces,
                             hipStream_t stream);
 
+hipError_t launch_copy_pages(const void* pairs, long n_pairs, int units_per_page, const void* src, void* dst,
+                             hipStream_t stream);
+
 }  // namespace hfx

@@ -200,6 +200,53 @@ def test_append_kv_is_bit_exact_and_feeds_attention(hb, oracle, idx, scale):
     err = np.abs(got - oracle.attention_batch(b))
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
 
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 1, 64), (12, 12, 128)])
+def test_copy_pages_is_bit_exact_and_attention_follows_the_pages(hb, oracle, Hq, Hkv, D):
+    """A request's pages move to another pool (bit for bit, nothing else touched); attention through the
+    destination pool and the new block table gives the very bits it gave through the source pool."""
+    import torch
+    rng = np.random.default_rng(31)
+    b = synth.make_batch(Hq, Hkv, D, [DECODE, PREFILL, DECODE], [1, 70, 1], [333, 150, 17], seed=31,
+                         name=f"copy-{Hq}-{Hkv}-{D}")
+    shape = hb.make_shape(Hq, Hkv, D, b.num_pages, 0.0)
+    src_ids = b.bt_pages.copy()                      # every page of every request
+    n_dst = len(src_ids) + 9
+    dst_ids = rng.permutation(n_dst)[:len(src_ids)].astype(np.int32)
+    dst_np = synth.f32_to_bf16_bits(rng.standard_normal((n_dst,) + b.pool.shape[1:]).astype(np.float32))
+    want = dst_np.copy()
+    oracle.copy_pages(Hkv, D, src_ids, dst_ids, b.pool, want)
+    src_dev = torch.from_numpy(b.pool.view(np.int16)).cuda()
+    dst_dev = torch.from_numpy(dst_np.view(np.int16)).cuda()
+    host_stage = torch.empty(8 * len(src_ids), dtype=torch.uint8, pin_memory=True)
+    dev_stage = torch.empty(8 * len(src_ids), dtype=torch.uint8, device="cuda")
+    hb.hfx_copy_pages(shape, src_dev, dst_dev, n_dst, src_ids, dst_ids, host_stage, dev_stage)
+    hb.hfx_copy_pages(shape, src_dev, dst_dev, n_dst, [], [], host_stage, dev_stage)       # no-op
+    torch.cuda.synchronize()
+    assert np.array_equal(dst_dev.cpu().numpy().view(np.uint16), want)
+    assert np.array_equal(src_dev.cpu().numpy().view(np.uint16), b.pool)
+
+    # inside one pool: move the last request's pages onto unused ids
+    used = set(b.bt_pages.tolist())
+    free = np.array([p for p in range(b.num_pages) if p not in used], np.int32)
+    r = 2
+    mine = b.bt_pages[b.bt_indptr[r]:b.bt_indptr[r + 1]]
+    if len(free) >= len(mine):
+        want2 = b.pool.copy()
+        oracle.copy_pages(Hkv, D, mine, free[:len(mine)], b.pool, want2)
+        hb.hfx_copy_pages(shape, src_dev, src_dev, b.num_pages, mine, free[:len(mine)], host_stage, dev_stage)
+        torch.cuda.synchronize()
+        assert np.array_equal(src_dev.cpu().numpy().view(np.uint16), want2)
+
+    # attention over the moved pages
+    first = hb.DeviceStep(b).run()
+    import copy
+    b2 = copy.copy(b)
+    b2.num_pages, b2.bt_pages, b2.pool = n_dst, dst_ids.copy(), want
+    second = hb.DeviceStep(b2, pool_dev=dst_dev).run()
+    torch.cuda.synchronize()
+    assert torch.equal(first, second)
+
+
 
 def test_device_side_errors(hb):
     import torch

@@ -211,3 +211,25 @@ def test_extra_reserved_pages_are_ignored(lib):
     d = fill(b)
     assert d["header"].n_bt == 3 + 4
     check_coverage(b, d)
+
+
+def test_copy_pages_validation(lib):
+    # every check below fails on the host before anything is enqueued, so dummy device addresses do
+    shape = hb.make_shape(8, 2, 64, 10, 0.0)
+    stage = np.zeros(64, np.uint8)
+    src, dst = 0x10000, 0x20000
+
+    def call(s_ids, d_ids, src_pool=src, dst_pool=dst, dst_pages=6, host=stage, dev=0x30000):
+        hb.hfx_copy_pages(shape, src_pool, dst_pool, dst_pages, s_ids, d_ids, host, dev, stage_bytes=64)
+
+    call([], [])                                           # nothing to do
+    for s_ids, d_ids, kw, code in [
+            ([10], [0], {}, hb.HFX_ERR_PAGE_ID), ([-1], [0], {}, hb.HFX_ERR_PAGE_ID),
+            ([0], [6], {}, hb.HFX_ERR_PAGE_ID), ([0, 1], [3, 3], {}, hb.HFX_ERR_PAGES),
+            ([0, 1], [2, 0], {"dst_pool": src, "dst_pages": 10}, hb.HFX_ERR_PAGES),
+            ([0], [1], {"src_pool": 0x10008}, hb.HFX_ERR_ALIGN),
+            (list(range(9)), list(range(9)), {"dst_pages": 10}, hb.HFX_ERR_BUFSIZE),
+            ([0], [1], {"dst_pages": 0}, hb.HFX_ERR_SHAPE)]:
+        with pytest.raises(hb.HfxError) as e:
+            call(s_ids, d_ids, **kw)
+        assert e.value.code == code, (s_ids, d_ids, kw)

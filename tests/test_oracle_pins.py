@@ -278,6 +278,32 @@ def test_append_writes_exactly_the_chunk_tokens(oracle):
     assert touched.sum() == 2 * T * 2 * 64
 
 
+def test_copy_pages_moves_whole_pages_and_nothing_else(oracle):
+    # pinned by numpy's fancy indexing, and end to end: a request un-paged through the destination
+    # pool and its new block table reads exactly what it read through the source pool
+    b = small_mixed(29, Hq=8, Hkv=2, D=64)
+    rng = np.random.default_rng(8)
+    r = 1
+    src_ids = b.bt_pages[b.bt_indptr[r]:b.bt_indptr[r + 1]].copy()
+    dst = f32_to_bf16_bits(rng.standard_normal((40,) + b.pool.shape[1:]).astype(np.float32))
+    before = dst.copy()
+    dst_ids = rng.permutation(40)[:len(src_ids)].astype(np.int32)
+    oracle.copy_pages(2, 64, src_ids, dst_ids, b.pool, dst)
+    want = before.copy()
+    want[dst_ids] = b.pool[src_ids]
+    assert np.array_equal(dst, want)
+    k0, v0 = brute.unpage(b, r)
+    import copy
+    b2 = copy.copy(b)
+    b2.pool, b2.num_pages = dst, 40
+    b2.bt_pages = b.bt_pages.copy()
+    b2.bt_pages[b.bt_indptr[r]:b.bt_indptr[r + 1]] = dst_ids
+    k1, v1 = brute.unpage(b2, r)
+    assert np.array_equal(k0, k1) and np.array_equal(v0, v1)
+    with pytest.raises(ValueError):
+        oracle.copy_pages(2, 64, [0], [40], b.pool, dst)
+
+
 def test_split_merge_identity_in_fp64():
     # (m, l, acc) partials over any partition of the keys merge to the one-pass result.
     rng = np.random.default_rng(6)
