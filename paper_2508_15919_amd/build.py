@@ -12,7 +12,10 @@ SOURCES = ["hfx_kernels.hip", "hfx_api.cpp", "hfx_plan.cpp", "hfx_sched.cpp"]
 # -fno-honor-nans: no floating-point operation in the kernels is ever fed a NaN (possibly-NaN scores
 # are masked through integer selects first), and without it every max carries a canonicalising twin.
 # Device code only: the host side validates its floating-point arguments with NaN tests.
+# The atomic optimizer is switched off: it rewrites thread 0's ticket fetch into a form that
+# waits for the counter's reply on the spot, and the reply is only needed an item later.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Xarch_device", "-fno-honor-nans",
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -387,12 +387,13 @@ struct TilePages {
   int pg[4];
 };
 
-__device__ __forceinline__ TilePages tile_pages(const int* bt, int last_page, int kt) {
+// bt: the step's whole stored block table; bt0: where the request's entries start
+__device__ __forceinline__ TilePages tile_pages(const int* __restrict__ bt, int bt0, int last_page, int kt) {
   TilePages t;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int lp = kt / HFX_PAGE + s;
-    t.pg[s] = bt[lp < last_page ? lp : last_page];
+    t.pg[s] = bt[bt0 + (lp < last_page ? lp : last_page)];
   }
   return t;
 }
@@ -552,110 +553,143 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
 // s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
 #define HFX_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
 
+// Work-queue tickets of a workgroup.  It holds the item it is processing, the item after it
+// (whose record is therefore known while the current item runs, so that a prefill item can
+// request the first tiles of its successor before it ends) and, in thread 0, the ticket after
+// that, fetched at the previous hand-over.  The first three tickets of a workgroup are its
+// index plus 0, 1 and 2 grids (the queue is in descending cost, so this deals the largest items
+// out evenly); later ones come from the atomic counter.
+struct Tickets {
+  int cur, nxt;
+  int pending;   // meaningful in thread 0 only: the counter's reply, an offset from 3 grids
+  int parity;
+};
+
+// Hand-over to the next item: thread 0 publishes the ticket it holds through LDS (two slots
+// alternate, so one barrier per hand-over is enough) and asks for the one after it.
+__device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
+  // the reply is first touched here, an item after it was asked for
+  if (threadIdx.x == 0) s_tk[t.parity] = 3 * (int)gridDim.x + t.pending;
+}
+// ... after a workgroup barrier that follows tickets_publish
+__device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk, int* ctrl) {
+  t.cur = t.nxt;
+  t.nxt = uniform(s_tk[t.parity]);
+  t.parity ^= 1;
+  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
+}
+// The barrier also frees the LDS of the finished item.
+__device__ __forceinline__ void tickets_advance(Tickets& t, int* s_tk, int* ctrl) {
+  tickets_publish(t, s_tk);
+  __syncthreads();
+  tickets_take(t, s_tk, ctrl);
+}
+
+// Wave-uniform description of where the workgroup's tile stream goes: the current prefill item
+// and, when the next item of this workgroup is a prefill item too, that one.
+struct TileStream {
+  int bt0;            // start of the current item's request in the stored block table
+  int last_page;
+  int g;              // kv-head
+  int end;            // first key past the current item's last (whole) tile
+  bool next_ok;
+  int bt0_n, last_n, g_n, kb_n;   // the same for the next item, and its first key
+};
+
+// Pages of the 64-key tile that starts `kt` keys into the stream (kt counts on past the end of
+// the current item into the next one's range; with no next prefill item the indices are clamped
+// into the current request and the data is never used).
+__device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, const TileStream& ts, int kt,
+                                                  int& g_out) {
+  const bool into_next = kt >= ts.end && ts.next_ok;
+  const int bt0 = into_next ? ts.bt0_n : ts.bt0;
+  const int lp = into_next ? ts.last_n : ts.last_page;
+  const int k = into_next ? ts.kb_n + (kt - ts.end) : kt;
+  g_out = into_next ? ts.g_n : ts.g;
+  return tile_pages(bt, bt0, lp, k);
+}
+
 // One 64-key tile from the LDS buffer `kcur`.  Order of the memory traffic: the V fragments of
 // the second half are requested first; once the last K operands of this tile have been read out
 // of LDS, the V fragments of the next tile's first half are requested and the copy of the K tile
 // two tiles ahead goes into `kfill` (three buffers rotate, so the buffer being filled was last
-// read one tile ago and every wavefront has passed a barrier since).  Loads return in order: by the
-// time this tile's second-half V fragments have arrived, the K tile requested one tile earlier
-// has landed too, so the barrier at the end needs no wait of its own.
+// read one tile ago and every wavefront has passed a barrier since).  "Next" and "two ahead" are
+// positions in the workgroup's tile stream: past the end of the item they are the first tiles of
+// the next prefill item.  Loads return in order: by the time this tile's second-half V fragments
+// have arrived, the K tile requested one tile earlier has landed too, so the barrier at the end
+// needs no wait of its own.
 template <int D>
 __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, VHalf<D>& vx, VHalf<D>& vy,
-                                             const char* kcur, char* kfill, const __bf16* pool, const int* bt,
-                                             int last_page, int kt, int wave_kend, int wave_pmin, int ctx_len,
-                                             int Hkv, int g, int k_lane, int v_lane, int j, float sl2, int wave,
-                                             int lane) {
+                                             const char* kcur, char* kfill, const __bf16* pool,
+                                             const int* __restrict__ bt, const TileStream& ts, int kt, int wave_kend, int wave_pmin,
+                                             int ctx_len, int Hkv, int k_lane, int v_lane, int j, float sl2,
+                                             int wave, int lane) {
   const bool active = kt < wave_kend;
   const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
   const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
-  // Every load below is issued unconditionally (past the end of the range the page indices are
+  // Every load below is issued unconditionally (past the end of the stream the page indices are
   // clamped, so the addresses stay valid and the data is simply not used): the wait counters the
   // compiler derives are compile-time constants, and a path that skipped a load would force
   // them to zero and stall the pipeline on every tile.
   KFrags<D> kf;
-  v_half_load<D>(vy, pool, tp.pg[2], tp.pg[3], Hkv, g, v_lane);
+  v_half_load<D>(vy, pool, tp.pg[2], tp.pg[3], Hkv, ts.g, v_lane);
   k_frags_read<D>(kf, kcur + k_lane);
   if (active) prefill_half<D>(w, vx, kf, masked, past_ctx, kt, ctx_len, j, sl2);
   k_frags_read<D>(kf, kcur + 1024 + k_lane);
-  tp = tile_pages(bt, last_page, kt + HFX_KEY_TILE);
-  v_half_load<D>(vx, pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
+  int g1, g2;
+  tp = stream_pages(bt, ts, kt + HFX_KEY_TILE, g1);
+  v_half_load<D>(vx, pool, tp.pg[0], tp.pg[1], Hkv, g1, v_lane);
   // The copy goes last: the compiler does not count it, so the waits it derives for the V
   // fragments above would otherwise also wait for a copy issued in front of them.
-  const TilePages ahead = tile_pages(bt, last_page, kt + 2 * HFX_KEY_TILE);
-  k_tile_async<D>(kfill, pool, ahead, Hkv, g, wave, lane);
+  const TilePages ahead = stream_pages(bt, ts, kt + 2 * HFX_KEY_TILE, g2);
+  k_tile_async<D>(kfill, pool, ahead, Hkv, g2, wave, lane);
   if (active) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
   else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
   __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
   asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
 }
 
+// What a wavefront derives from a prefill item: its q-head and rows, and the key ranges that
+// decide whether a tile is worked on and whether it needs masks.
+struct WaveRows {
+  int head, qrow, wave_kend, wave_pmin;
+  bool store;    // qrow is a real row of the chunk
+};
+
 template <int D>
-__device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = uniform(tid >> 6);
-  const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
-  const int G = Hq / Hkv;
-  const int head = it.h0 + wave % it.hn;
-  const int g = it.h0 / G;
+__device__ __forceinline__ WaveRows wave_rows(const HfxItem& it, int wave, int n) {
+  WaveRows r;
+  r.head = it.h0 + wave % it.hn;
   const int r0 = it.row0 + (wave / it.hn) * HFX_WAVE_ROWS;
-  const int n = lane & 31, j = lane >> 5;
-  const int p = rq.ctx_len - rq.q_len;
-  const int wave_kend = r0 < rq.q_len ? p + min(r0 + HFX_WAVE_ROWS, rq.q_len) : 0;   // keys >= this: nothing to do
-  const int wave_pmin = p + r0;                                 // keys <= this are visible to every row
-  const float sl2 = H->softmax_scale * 1.4426950408889634f;
-  const int qrow = r0 + n;
-  const int qc = qrow < rq.q_len ? qrow : rq.q_len - 1;
+  const int p = it.rq.ctx_len - it.rq.q_len;
+  r.wave_kend = r0 < it.rq.q_len ? p + min(r0 + HFX_WAVE_ROWS, it.rq.q_len) : 0;   // keys >= this: nothing to do
+  r.wave_pmin = p + r0;                                                            // keys <= this are visible to every row
+  r.qrow = r0 + n;
+  r.store = r.qrow < it.rq.q_len;
+  return r;
+}
 
-  PrefillWave<D> w;
-  w.pos = p + qc;
-  {
-    const __bf16* qp = a.q + (((long)rq.q_start + qc) * Hq + head) * D + j * 8;
+// Q^T operand fragments of this lane's row (rows past the chunk read the last row and are never stored)
+template <int D>
+__device__ __forceinline__ void q_load(PrefillWave<D>& w, const KArgs& a, const HfxItem& it, const WaveRows& r, int Hq,
+                                       int j) {
+  const int qc = r.store ? r.qrow : it.rq.q_len - 1;
+  w.pos = it.rq.ctx_len - it.rq.q_len + qc;
+  const __bf16* qp = a.q + (((long)it.rq.q_start + qc) * Hq + r.head) * D + j * 8;
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) w.qf[kk] = ld16(qp + kk * 16);
-  }
-#pragma unroll
-  for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) w.o[b][v] = 0.f;
-  w.m = NEG_INF;
-  w.l = 0.f;
+  for (int kk = 0; kk < D / 16; ++kk) w.qf[kk] = ld16(qp + kk * 16);
+}
 
-  const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
-  const int last_page = rq.n_pages - 1;
-  // row of this lane's key inside a 32-key half of the LDS tile
-  const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
-  const int k_lane = (j * 32 + krow) * 16;
-  const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
-
-  TilePages tp = tile_pages(bt, last_page, it.kb);
-  k_tile_async<D>(smem, a.pool, tp, Hkv, g, wave, lane);
-  {
-    const TilePages t1 = tile_pages(bt, last_page, it.kb + HFX_KEY_TILE);
-    k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, t1, Hkv, g, wave, lane);
-  }
-  VHalf<D> vx, vy;
-  v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, g, v_lane);
-  HFX_WAIT_VMCNT(0);
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  int cur = 0;   // byte offset of the K buffer holding tile kt; the one two ahead is refilled
-  for (int kt = it.kb; kt < it.ke; kt += HFX_KEY_TILE) {
-    int fill = cur + 2 * Smem<D>::kKBytes;
-    if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
-    prefill_tile<D>(w, tp, vx, vy, smem + cur, smem + fill, a.pool, bt, last_page, kt, wave_kend, wave_pmin,
-                    rq.ctx_len, Hkv, g, k_lane, v_lane, j, sl2, wave, lane);
-    cur += Smem<D>::kKBytes;
-    if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
-  }
-  HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the range
-
+// Result of a finished item: normalised bf16 rows, or (m, l, acc) partial rows when the item is one split of a group.
+template <int D>
+__device__ __forceinline__ void prefill_store(const KArgs& a, const HfxHeader* H, const HfxItem& it, const WaveRows& r,
+                                              const PrefillWave<D>& w, int Hq, int wave, int n, int j) {
   // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
   const float lsum = sum_xor32(w.l);
   if (it.group < 0) {
-    if (qrow < rq.q_len) {
+    if (r.store) {
       const float inv = 1.0f / lsum;
-      __bf16* dst = a.out + (((long)rq.q_start + qrow) * Hq + head) * D + 4 * j;
+      __bf16* dst = a.out + (((long)it.rq.q_start + r.qrow) * Hq + r.head) * D + 4 * j;
 #pragma unroll
       for (int b = 0; b < D / 32; ++b)
 #pragma unroll
@@ -685,11 +719,118 @@ __device__ void prefill_item(const KArgs& a, const HfxHeader* H, const HfxItem& 
   }
 }
 
+// Runs the prefill item t.cur and, for as long as the workgroup's next item is a prefill item as
+// well, carries straight on into it: the tile pipeline (K copy two tiles ahead, V fragments one
+// tile ahead) does not drain between items, only the per-row state (Q, O, m, l) is swapped.
+// Returns with t.cur at the first item it did not process.
+template <int D>
+__device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* __restrict__ items, int n_items,
+                            Tickets& t, int* s_tk, int* ctrl, char* smem) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
+  const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
+  const int G = Hq / Hkv;
+  const int n = lane & 31, j = lane >> 5;
+  const float sl2 = H->softmax_scale * 1.4426950408889634f;
+  const int* bt_all = reinterpret_cast<const int*>(a.desc + H->off_bt);
+  // row of this lane's key inside a 32-key half of the LDS tile
+  const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
+  const int k_lane = (j * 32 + krow) * 16;
+  const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
+
+  HfxItem it = items[t.cur];
+  HfxItem nx = items[t.nxt < n_items ? t.nxt : t.cur];
+  TileStream ts;
+  auto set_stream = [&]() {
+    ts.bt0 = it.rq.bt_start;
+    ts.last_page = it.rq.n_pages - 1;
+    ts.g = it.h0 / G;
+    ts.end = it.kb + (it.ke - it.kb + HFX_KEY_TILE - 1) / HFX_KEY_TILE * HFX_KEY_TILE;
+    ts.next_ok = t.nxt < n_items && nx.type == HFX_ITEM_PREFILL;
+    ts.bt0_n = nx.rq.bt_start;
+    ts.last_n = nx.rq.n_pages - 1;
+    ts.g_n = nx.h0 / G;
+    ts.kb_n = nx.kb;
+  };
+  set_stream();
+
+  PrefillWave<D> w;
+  WaveRows wr = wave_rows<D>(it, wave, n);
+  q_load<D>(w, a, it, wr, Hq, j);
+#pragma unroll
+  for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w.o[b][v] = 0.f;
+  w.m = NEG_INF;
+  w.l = 0.f;
+
+  // cold start: the first two tiles of the stream and the first V fragments
+  int kt = it.kb;
+  TilePages tp = tile_pages(bt_all, ts.bt0, ts.last_page, kt);
+  k_tile_async<D>(smem, a.pool, tp, Hkv, ts.g, wave, lane);
+  {
+    int g1;
+    const TilePages t1 = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, g1);
+    k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, t1, Hkv, g1, wave, lane);
+  }
+  VHalf<D> vx, vy;
+  v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, ts.g, v_lane);
+  HFX_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int cur = 0;   // byte offset of the K buffer holding the current tile; the one two ahead is refilled
+  for (;;) {
+    int fill = cur + 2 * Smem<D>::kKBytes;
+    if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
+    // The ticket after next was asked for at the last hand-over and has arrived by now.  It is
+    // published here, ahead of the barrier that ends the item's first tile, so that the hand-over
+    // at the end of the item needs no barrier of its own (which would wait for the result rows on
+    // their way to memory).
+    if (kt == it.kb) tickets_publish(t, s_tk);
+    prefill_tile<D>(w, tp, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
+                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane);
+    cur += Smem<D>::kKBytes;
+    if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
+    kt += HFX_KEY_TILE;
+    if (kt < it.ke) continue;
+
+    // hand-over: the item is finished; its successor's first tiles are already on their way
+    const bool carry_on = ts.next_ok;
+    prefill_store<D>(a, H, it, wr, w, Hq, wave, n, j);
+    tickets_take(t, s_tk, ctrl);
+    if (!carry_on) break;
+    it = nx;
+    nx = items[t.nxt < n_items ? t.nxt : t.cur];
+    set_stream();
+    wr = wave_rows<D>(it, wave, n);
+    q_load<D>(w, a, it, wr, Hq, j);
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) w.o[b][v] = 0.f;
+    w.m = NEG_INF;
+    w.l = 0.f;
+    kt = it.kb;
+    if (kt + HFX_KEY_TILE >= it.ke) {
+      // a one-tile item: the stream position after it belongs to an item that was not known yet
+      // when that position's copy was issued; request it again, now with the right pages
+      int g1;
+      int nb = cur + Smem<D>::kKBytes;
+      if (nb >= 3 * Smem<D>::kKBytes) nb = 0;
+      const TilePages t1 = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, g1);
+      k_tile_async<D>(smem + nb, a.pool, t1, Hkv, g1, wave, lane);
+    }
+  }
+  HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the stream
+  __syncthreads();     // ... by every wavefront, before the LDS is used for anything else
+}
+
 // ----------------------------------------------------------------------------------------------
 // The persistent kernel: workgroups pull items in descending modelled cost until the queue is
-// empty; the fetch of the next item is issued before the current one is processed so that its
-// latency hides behind the item's own loads.  The queue head lives in the descriptor; the last
-// workgroup to leave restores it to zero so the descriptor can serve the next launch.
+// empty.  A workgroup always knows its next item (see Tickets).  The queue head lives in the
+// descriptor; the last workgroup to leave restores it to zero so the descriptor can serve the
+// next launch.
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
@@ -704,25 +845,28 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   a.ws = ws;
   a.out = out;
   __shared__ __attribute__((aligned(1024))) char smem[Smem<D>::kBytes];
-  __shared__ int s_next;
+  __shared__ int s_tk[2];
   const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const int n_items = H->n_items;
-  if (threadIdx.x == 0) s_next = atomicAdd(&ctrl[0], 1);
-  __syncthreads();
-  for (;;) {
-    const int idx = uniform(s_next);
-    if (idx >= n_items) break;
-    __syncthreads();   // s_next has been read by all; LDS of the previous item is free
-    int nxt = 0;
-    if (threadIdx.x == 0) nxt = atomicAdd(&ctrl[0], 1);
-    const HfxItem it = items[idx];
-    const HfxReq rq = it.rq;
-    if (it.type == HFX_ITEM_DECODE) decode_item<D>(a, H, it, rq, smem);
-    else prefill_item<D>(a, H, it, rq, smem);
-    if (threadIdx.x == 0) s_next = nxt;
-    __syncthreads();
+  Tickets t;
+  t.cur = (int)blockIdx.x;
+  t.nxt = (int)(blockIdx.x + gridDim.x);
+  t.pending = (int)blockIdx.x - (int)gridDim.x;
+  t.parity = 0;
+  while (t.cur < n_items) {
+    if (items[t.cur].type == HFX_ITEM_DECODE) {
+      const HfxItem it = items[t.cur];
+      decode_item<D>(a, H, it, it.rq, smem);
+      tickets_advance(t, s_tk, &ctrl[0]);
+    } else {
+      prefill_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem);
+    }
   }
+  // the ticket fetched last is never used; it must have reached the counter before this
+  // workgroup reports itself finished, or it could land after the reset below
+  HFX_WAIT_VMCNT(0);
+  asm volatile("" ::: "memory");
   if (threadIdx.x == 0) {
     const int done = atomicAdd(&ctrl[1], 1);
     if (done == (int)gridDim.x - 1) {
