@@ -173,6 +173,38 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __res
 // result layout, each lane ends up holding 8 consecutive tokens of one page -- exactly the
 // 16 bytes of a dimension-major V row that the second contraction needs, with no shuffles.
 // ----------------------------------------------------------------------------------------------
+// Work-queue tickets of a workgroup.  It holds the item it is processing, the item after it
+// (whose record is therefore known while the current item runs, so that a prefill item can
+// request the first tiles of its successor before it ends) and, in thread 0, the ticket after
+// that, fetched at the previous hand-over.  The first three tickets of a workgroup are its
+// index plus 0, 1 and 2 grids (the queue is in descending cost, so this deals the largest items
+// out evenly); later ones come from the atomic counter.
+struct Tickets {
+  int cur, nxt;
+  int pending;   // meaningful in thread 0 only: the counter's reply, an offset from 3 grids
+  int parity;
+};
+
+// Hand-over to the next item: thread 0 publishes the ticket it holds through LDS (two slots
+// alternate, so one barrier per hand-over is enough) and asks for the one after it.
+__device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
+  // the reply is first touched here, an item after it was asked for
+  if (threadIdx.x == 0) s_tk[t.parity] = 3 * (int)gridDim.x + t.pending;
+}
+// ... after a workgroup barrier that follows tickets_publish
+__device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk, int* ctrl) {
+  t.cur = t.nxt;
+  t.nxt = uniform(s_tk[t.parity]);
+  t.parity ^= 1;
+  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
+}
+// The barrier also frees the LDS of the finished item.
+__device__ __forceinline__ void tickets_advance(Tickets& t, int* s_tk, int* ctrl) {
+  tickets_publish(t, s_tk);
+  __syncthreads();
+  tickets_take(t, s_tk, ctrl);
+}
+
 template <int D>
 struct PairRegs {
   bf16x8 ka[D / 32], kb[D / 32], v[D / 16];
@@ -235,38 +267,53 @@ __device__ __forceinline__ void decode_compute(PairRegs<D>& r, const bf16x8* qf,
   }
 }
 
+// What a wavefront derives from a decode item: its kv-head, its share of the page pairs, and the
+// pages of its first two pairs.
+struct DecodeWave {
+  int g;          // kv-head
+  int step;       // pages between two pairs of this wavefront
+  int pp, pe;     // next page (pair-aligned) and end of the item's page range
+  int tend;       // tokens of the context that the item may see (end of its range or of the context)
+  int bt0, last_page;
+  int a0, a1, b0, b1;   // page ids of the pair at pp and of the one after it
+};
+
+__device__ __forceinline__ int decode_page(const int* __restrict__ bt, const DecodeWave& d, int i) {
+  return bt[d.bt0 + (i < d.last_page ? i : d.last_page)];
+}
+
+__device__ __forceinline__ DecodeWave decode_wave(const int* __restrict__ bt, const HfxItem& it, int wave) {
+  DecodeWave d;
+  const int HW = it.hn, TW = 4 / HW;
+  d.g = it.h0 + wave % HW;
+  d.step = 2 * TW;
+  d.pp = it.kb + 2 * (wave / HW);
+  d.pe = it.ke;
+  d.tend = min(it.ke * HFX_PAGE, it.rq.ctx_len);
+  d.bt0 = it.rq.bt_start;
+  d.last_page = it.rq.n_pages - 1;
+  d.a0 = decode_page(bt, d, d.pp);
+  d.a1 = decode_page(bt, d, d.pp + 1);
+  d.b0 = decode_page(bt, d, d.pp + d.step);
+  d.b1 = decode_page(bt, d, d.pp + d.step + 1);
+  return d;
+}
+
+// Runs the decode item t.cur and carries on for as long as the workgroup's next item is a decode
+// item too: the first KV pair of the next item is requested before the current item's partial
+// results are combined and stored, so the KV stream of a workgroup does not stop between items.
+// Returns with t.cur at the first item it did not process.
 template <int D>
-__device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& it, const HfxReq& rq, char* smem) {
+__device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __restrict__ items, int n_items,
+                           Tickets& t, int* s_tk, int* ctrl, char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
   const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
   const int G = Hq / Hkv;
-  const int HW = it.hn, TW = 4 / HW;
-  const int hw = wave % HW, tw = wave / HW;
-  const int g = it.h0 + hw;
   const int n = lane & 15, j = lane >> 4;
   const float sl2 = H->softmax_scale * 1.4426950408889634f;
-
-  bf16x8 qf[D / 32];
-  {
-    const int hh = n < G ? n : G - 1;
-    const __bf16* qrow = a.q + ((long)rq.q_start * Hq + g * G + hh) * D + j * 8;
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) {
-      bf16x8 t = ld16(qrow + kk * 32);
-      qf[kk] = keep_first(t, n < G ? 8 : 0);
-    }
-  }
-  f32x4 o[D / 16];
-#pragma unroll
-  for (int b = 0; b < D / 16; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = NEG_INF, l = 0.f;
-
-  const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt) + rq.bt_start;
-  const int last_page = rq.n_pages - 1;
-  const int pe = it.ke;
-  const int tend = min(pe * HFX_PAGE, rq.ctx_len);
+  const int* bt = reinterpret_cast<const int*>(a.desc + H->off_bt);
   // K rows of the two score tiles: row rho of tile A is (page rho>>3, token ((rho>>2)&1)*8 + (rho&3)),
   // tile B the same + 4 tokens.  V: lane group j reads tokens (j&1)*8.. of page j>>1 for row d = 16b + n.
   const int k_sel = n >> 3;
@@ -274,96 +321,122 @@ __device__ void decode_item(const KArgs& a, const HfxHeader* H, const HfxItem& i
   const int v_sel = j >> 1;
   const int v_off = n * 16 + (j & 1) * 8;
   const int tok_lane = (j >> 1) * 16 + (j & 1) * 8;   // first of this lane's 8 tokens inside the pair
-  const int step = 2 * TW;
 
-  // page ids are fetched one pair ahead of the KV loads that need them
-  auto page_id = [&](int i) { return bt[i < last_page ? i : last_page]; };
+  HfxItem it = items[t.cur];
+  DecodeWave d = decode_wave(bt, it, wave);
   PairRegs<D> r0, r1;
-  int pp = it.kb + 2 * tw;
-  int a0 = 0, a1 = 0, b0 = 0, b1 = 0;
-  if (pp < pe) {
-    a0 = page_id(pp);
-    a1 = page_id(pp + 1);
-    decode_load<D>(r0, a.pool, a0, a1, Hkv, g, k_sel, k_off, v_sel, v_off);
-  }
-  if (pp + step < pe) {
-    b0 = page_id(pp + step);
-    b1 = page_id(pp + step + 1);
-  }
-  while (pp < pe) {
-    if (pp + step < pe) decode_load<D>(r1, a.pool, b0, b1, Hkv, g, k_sel, k_off, v_sel, v_off);
-    if (pp + 2 * step < pe) {
-      a0 = page_id(pp + 2 * step);
-      a1 = page_id(pp + 2 * step + 1);
-    }
-    {
-      const int nv = tend - (pp * HFX_PAGE + tok_lane);
-      if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r0, qf, o, m, l, sl2, 8);
-      else decode_compute<D>(r0, qf, o, m, l, sl2, nv);
-    }
-    pp += step;
-    if (pp >= pe) break;
-    if (pp + step < pe) decode_load<D>(r0, a.pool, a0, a1, Hkv, g, k_sel, k_off, v_sel, v_off);
-    if (pp + 2 * step < pe) {
-      b0 = page_id(pp + 2 * step);
-      b1 = page_id(pp + 2 * step + 1);
-    }
-    {
-      const int nv = tend - (pp * HFX_PAGE + tok_lane);
-      if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r1, qf, o, m, l, sl2, 8);
-      else decode_compute<D>(r1, qf, o, m, l, sl2, nv);
-    }
-    pp += step;
-  }
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-
-  // wavefront partial -> LDS: part[wave][head n][D + 4]; o[b][v] is dimension 16b + 4j + v
-  constexpr int PS = Smem<D>::kPartStride;
-  float* part = reinterpret_cast<float*>(smem);
-  if (n < G) {
-    float* dst = part + ((wave * 16 + n) * PS);
+  if (d.pp < d.pe) decode_load<D>(r0, a.pool, d.a0, d.a1, Hkv, d.g, k_sel, k_off, v_sel, v_off);
+  bf16x8 qf[D / 32];
+  auto q_load = [&](const HfxItem& item, int g) {
+    const int hh = n < G ? n : G - 1;
+    const __bf16* qrow = a.q + ((long)item.rq.q_start * Hq + g * G + hh) * D + j * 8;
 #pragma unroll
-    for (int b = 0; b < D / 16; ++b) *reinterpret_cast<f32x4*>(dst + b * 16 + 4 * j) = o[b];
-    if (j == 0) {
-      dst[D] = m;
-      dst[D + 1] = l;
+    for (int kk = 0; kk < D / 32; ++kk) {
+      bf16x8 tq = ld16(qrow + kk * 32);
+      qf[kk] = keep_first(tq, n < G ? 8 : 0);
     }
-  }
-  __syncthreads();
+  };
+  q_load(it, d.g);
 
-  // combine the TW token partitions of each head; row = hwi * G + hh
-  const int rows = HW * G;
-  float* ws_acc = a.ws;
-  float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
-  constexpr int C4 = D / 4;
-  for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
-    const int row = idx / C4, d4 = (idx % C4) * 4;
-    const int hwi = row / G, hh = row % G;
-    float mm = NEG_INF;
-    for (int t = 0; t < TW; ++t) mm = fmaxf(mm, part[((t * HW + hwi) * 16 + hh) * PS + D]);
-    float ll = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int t = 0; t < TW; ++t) {
-      const float* src = part + ((t * HW + hwi) * 16 + hh) * PS;
-      const float w = fast_exp2(src[D] - mm);
-      ll += src[D + 1] * w;
-      acc += *reinterpret_cast<const f32x4*>(src + d4) * w;
-    }
-    if (it.group < 0) {
-      const float inv = 1.0f / ll;
-      bf16x4 ob;
+  for (;;) {
+    // the record of the next item and, if it is a decode item, this wavefront's share of it
+    const HfxItem nx = items[t.nxt < n_items ? t.nxt : t.cur];
+    const bool carry_on = t.nxt < n_items && nx.type == HFX_ITEM_DECODE;
+    const DecodeWave dn = decode_wave(bt, nx, wave);
+
+    f32x4 o[D / 16];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(acc[e] * inv);
-      *reinterpret_cast<bf16x4*>(a.out + ((long)rq.q_start * Hq + it.h0 * G + row) * D + d4) = ob;
-    } else {
-      const long pr = (long)it.slot_row + row;
-      *reinterpret_cast<f32x4*>(ws_acc + pr * D + d4) = acc;
-      if (d4 == 0) {
-        ws_ml[pr * 2] = mm;
-        ws_ml[pr * 2 + 1] = ll;
+    for (int b = 0; b < D / 16; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m = NEG_INF, l = 0.f;
+    const int step = d.step, pe = d.pe, tend = d.tend, g = d.g;
+    int pp = d.pp;
+    int a0 = d.a0, a1 = d.a1, b0 = d.b0, b1 = d.b1;
+    // page ids are fetched one pair ahead of the KV loads that need them
+    while (pp < pe) {
+      if (pp + step < pe) decode_load<D>(r1, a.pool, b0, b1, Hkv, g, k_sel, k_off, v_sel, v_off);
+      if (pp + 2 * step < pe) {
+        a0 = decode_page(bt, d, pp + 2 * step);
+        a1 = decode_page(bt, d, pp + 2 * step + 1);
+      }
+      {
+        const int nv = tend - (pp * HFX_PAGE + tok_lane);
+        if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r0, qf, o, m, l, sl2, 8);
+        else decode_compute<D>(r0, qf, o, m, l, sl2, nv);
+      }
+      pp += step;
+      if (pp >= pe) break;
+      if (pp + step < pe) decode_load<D>(r0, a.pool, a0, a1, Hkv, g, k_sel, k_off, v_sel, v_off);
+      if (pp + 2 * step < pe) {
+        b0 = decode_page(bt, d, pp + 2 * step);
+        b1 = decode_page(bt, d, pp + 2 * step + 1);
+      }
+      {
+        const int nv = tend - (pp * HFX_PAGE + tok_lane);
+        if ((pp + 2) * HFX_PAGE <= tend) decode_compute<D>(r1, qf, o, m, l, sl2, 8);
+        else decode_compute<D>(r1, qf, o, m, l, sl2, nv);
+      }
+      pp += step;
+    }
+    // both register sets and the Q operand are free now: start on the next item
+    if (carry_on) {
+      if (dn.pp < dn.pe) decode_load<D>(r0, a.pool, dn.a0, dn.a1, Hkv, dn.g, k_sel, k_off, v_sel, v_off);
+      q_load(nx, dn.g);
+    }
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+
+    // wavefront partial -> LDS: part[wave][head n][D + 4]; o[b][v] is dimension 16b + 4j + v
+    constexpr int PS = Smem<D>::kPartStride;
+    float* part = reinterpret_cast<float*>(smem);
+    if (n < G) {
+      float* dst = part + ((wave * 16 + n) * PS);
+#pragma unroll
+      for (int b = 0; b < D / 16; ++b) *reinterpret_cast<f32x4*>(dst + b * 16 + 4 * j) = o[b];
+      if (j == 0) {
+        dst[D] = m;
+        dst[D + 1] = l;
       }
     }
+    __syncthreads();
+
+    // combine the TW token partitions of each head; row = hwi * G + hh
+    const int HW = it.hn, TW = 4 / HW;
+    const int rows = HW * G;
+    float* ws_acc = a.ws;
+    float* ws_ml = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ws) + H->ws_off_ml);
+    constexpr int C4 = D / 4;
+    for (int idx = tid; idx < rows * C4; idx += HFX_WG_THREADS) {
+      const int row = idx / C4, d4 = (idx % C4) * 4;
+      const int hwi = row / G, hh = row % G;
+      float mm = NEG_INF;
+      for (int tt = 0; tt < TW; ++tt) mm = fmaxf(mm, part[((tt * HW + hwi) * 16 + hh) * PS + D]);
+      float ll = 0.f;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int tt = 0; tt < TW; ++tt) {
+        const float* src = part + ((tt * HW + hwi) * 16 + hh) * PS;
+        const float wgt = fast_exp2(src[D] - mm);
+        ll += src[D + 1] * wgt;
+        acc += *reinterpret_cast<const f32x4*>(src + d4) * wgt;
+      }
+      if (it.group < 0) {
+        const float inv = 1.0f / ll;
+        bf16x4 ob;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(acc[e] * inv);
+        *reinterpret_cast<bf16x4*>(a.out + ((long)it.rq.q_start * Hq + it.h0 * G + row) * D + d4) = ob;
+      } else {
+        const long pr = (long)it.slot_row + row;
+        *reinterpret_cast<f32x4*>(ws_acc + pr * D + d4) = acc;
+        if (d4 == 0) {
+          ws_ml[pr * 2] = mm;
+          ws_ml[pr * 2 + 1] = ll;
+        }
+      }
+    }
+    tickets_advance(t, s_tk, ctrl);   // its barrier also frees the LDS partials
+    if (!carry_on) break;
+    it = nx;
+    d = dn;
   }
 }
 
@@ -552,38 +625,6 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
 
 // s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
 #define HFX_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
-
-// Work-queue tickets of a workgroup.  It holds the item it is processing, the item after it
-// (whose record is therefore known while the current item runs, so that a prefill item can
-// request the first tiles of its successor before it ends) and, in thread 0, the ticket after
-// that, fetched at the previous hand-over.  The first three tickets of a workgroup are its
-// index plus 0, 1 and 2 grids (the queue is in descending cost, so this deals the largest items
-// out evenly); later ones come from the atomic counter.
-struct Tickets {
-  int cur, nxt;
-  int pending;   // meaningful in thread 0 only: the counter's reply, an offset from 3 grids
-  int parity;
-};
-
-// Hand-over to the next item: thread 0 publishes the ticket it holds through LDS (two slots
-// alternate, so one barrier per hand-over is enough) and asks for the one after it.
-__device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
-  // the reply is first touched here, an item after it was asked for
-  if (threadIdx.x == 0) s_tk[t.parity] = 3 * (int)gridDim.x + t.pending;
-}
-// ... after a workgroup barrier that follows tickets_publish
-__device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk, int* ctrl) {
-  t.cur = t.nxt;
-  t.nxt = uniform(s_tk[t.parity]);
-  t.parity ^= 1;
-  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
-}
-// The barrier also frees the LDS of the finished item.
-__device__ __forceinline__ void tickets_advance(Tickets& t, int* s_tk, int* ctrl) {
-  tickets_publish(t, s_tk);
-  __syncthreads();
-  tickets_take(t, s_tk, ctrl);
-}
 
 // Wave-uniform description of where the workgroup's tile stream goes: the current prefill item
 // and, when the next item of this workgroup is a prefill item too, that one.
@@ -856,9 +897,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   t.parity = 0;
   while (t.cur < n_items) {
     if (items[t.cur].type == HFX_ITEM_DECODE) {
-      const HfxItem it = items[t.cur];
-      decode_item<D>(a, H, it, it.rq, smem);
-      tickets_advance(t, s_tk, &ctrl[0]);
+      decode_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem);
     } else {
       prefill_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem);
     }
