@@ -684,7 +684,8 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
   // fragments above would otherwise also wait for a copy issued in front of them.
   const TilePages ahead = stream_pages(bt, ts, kt + 2 * HFX_KEY_TILE, g2);
   k_tile_async<D>(kfill, pool, ahead, Hkv, g2, wave, lane);
-  if (active) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
+  // on the diagonal the second 32 keys may lie past every row of the wavefront
+  if (kt + 32 < wave_kend) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
   else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
   __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
   asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
