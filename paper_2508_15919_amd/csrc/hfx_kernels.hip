@@ -664,7 +664,7 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
                                              const char* kcur, char* kfill, const __bf16* pool,
                                              const int* __restrict__ bt, const TileStream& ts, int kt, int wave_kend, int wave_pmin,
                                              int ctx_len, int Hkv, int k_lane, int v_lane, int j, float sl2,
-                                             int wave, int lane) {
+                                             int wave, int lane, bool publish, const Tickets& t, int* s_tk) {
   const bool active = kt < wave_kend;
   const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
   const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
@@ -687,6 +687,15 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
   // on the diagonal the second 32 keys may lie past every row of the wavefront
   if (kt + 32 < wave_kend) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
   else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
+  if (publish) {
+    // First tile of an item: the ticket asked for at the last hand-over is published ahead of this
+    // tile's barrier, so that the hand-over at the end of the item needs no barrier of its own.
+    // It is done here, at the end of the tile, because reading the counter's reply makes the
+    // wavefront wait for everything it has in flight, and by now the result rows of the previous
+    // item have long reached memory.
+    tickets_publish(t, s_tk);
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the LDS write has been performed
+  }
   __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
   asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
 }
@@ -825,13 +834,8 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   for (;;) {
     int fill = cur + 2 * Smem<D>::kKBytes;
     if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
-    // The ticket after next was asked for at the last hand-over and has arrived by now.  It is
-    // published here, ahead of the barrier that ends the item's first tile, so that the hand-over
-    // at the end of the item needs no barrier of its own (which would wait for the result rows on
-    // their way to memory).
-    if (kt == it.kb) tickets_publish(t, s_tk);
     prefill_tile<D>(w, tp, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
-                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane);
+                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane, kt == it.kb, t, s_tk);
     cur += Smem<D>::kKBytes;
     if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
     kt += HFX_KEY_TILE;
