@@ -1,8 +1,9 @@
 // Device code of libhfxattn for gfx950 (MI355X): one persistent kernel that drains the
 // cost-ordered work items of a scheduled step -- decode ranges (HBM-bound streaming of KV
-// pages, HFX Section 2.1 "generation phase") and prefill tiles (dense bf16 MFMA contraction
-// with a causal mask, Section 2.1 "prompt phase") -- plus the split merge and the page
-// gather hook.  Wavefronts are 64 lanes wide; every tiling below is written for that.
+// pages: the token-generation phase of HFX Section 2.1) and prefill tiles (dense bf16 MFMA
+// contraction with a causal mask: its prompt phase) -- plus the split merge, the page gather
+// hook, the KV append and the page copy.  Wavefronts are 64 lanes wide; every tiling below is
+// written for that.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
