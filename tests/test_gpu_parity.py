@@ -160,6 +160,36 @@ def test_head_layouts_and_ragged_lengths(hb, oracle, Hq, Hkv, D):
     check_full(hb, oracle, synth.make_batch(Hq, Hkv, D, kinds, ql, cl, 100 + Hq + D, extra_pages_per_request=1))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_steps(hb, oracle, seed):
+    """Random shapes and length mixes: one-tile and many-tile prefill items and decode ranges of all
+    sizes follow each other in every order in a workgroup's queue."""
+    rng = np.random.default_rng(1000 + seed)
+    Hq, Hkv, D = [(32, 8, 128), (8, 8, 64), (16, 2, 128), (4, 1, 64), (24, 8, 128), (32, 4, 64), (8, 2, 128),
+                  (16, 16, 128)][seed]
+    R = int(rng.integers(1, 48))
+    kinds, ql, cl = [], [], []
+    for _ in range(R):
+        if rng.random() < 0.5:
+            kinds.append(DECODE); ql.append(1); cl.append(int(rng.choice([1, 2, 15, 16, 17, 31, 33, 257, 1000, 3000, 6000])))
+        else:
+            q = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 100, 129, 300]))
+            prior = int(rng.choice([0, 0, 1, 16, 63, 64, 100, 700]))
+            kinds.append(PREFILL); ql.append(q); cl.append(q + prior)
+    check_full(hb, oracle, synth.make_batch(Hq, Hkv, D, kinds, ql, cl, 2000 + seed, name=f"random-{seed}"))
+
+
+def test_many_short_items_in_a_row(hb, oracle):
+    """Far more items than resident workgroups, almost all of them one tile long: every workgroup chains
+    through dozens of hand-overs, first on its statically dealt items and then on counter tickets."""
+    rng = np.random.default_rng(77)
+    R = 700
+    kinds = [PREFILL if i % 3 else DECODE for i in range(R)]
+    ql = [int(rng.integers(1, 70)) if k == PREFILL else 1 for k in kinds]
+    cl = [q if k == PREFILL else int(rng.integers(1, 200)) for k, q in zip(kinds, ql)]
+    check_full(hb, oracle, synth.make_batch(32, 8, 128, kinds, ql, cl, 78, name="many-short"))
+
+
 def test_shared_prefix_pages(hb, oracle):
     b = synth.make_batch(32, 8, 128, [DECODE, DECODE, PREFILL], [1, 1, 40], [300, 300, 296], 13)
     n = 16
