@@ -302,7 +302,7 @@ ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row
 REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
                                               "pad0", "pad1")])
 GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "type", "req", "h0", "hn",
-                                                "row0")])
+                                                "row0", "q_start", "q_len")])
 
 
 def parse_desc(host_desc: np.ndarray) -> dict:

@@ -140,8 +140,8 @@ hfx_status hfx_mixed_paged_attention(const hfx_shape* shape, const void* q, cons
   st = persistent_grid(h.head_dim, &grid);
   if (st != HFX_OK) return st;
   if (grid > h.n_items) grid = h.n_items;
-  if (hfx::launch_mixed_attention(h.head_dim, grid, h.n_units, h.off_ctrl, device_desc, q, kv_pool, workspace, out,
-                                  static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (hfx::launch_mixed_attention(h, grid, device_desc, q, kv_pool, workspace, out, static_cast<hipStream_t>(stream)) !=
+      hipSuccess)
     return HFX_ERR_DEVICE;
   return HFX_OK;
 }

@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 9u
+#define HFX_DESC_VERSION 10u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -70,4 +70,5 @@ struct HfxGroup {
   int32_t base_row;
   int32_t rows_per_split;
   int32_t type, req, h0, hn, row0;
+  int32_t q_start, q_len;       /* of the request, so that the merge launch needs no third table */
 };

@@ -79,18 +79,20 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 // splits one thread takes them all (8 rows per workgroup).
 // ----------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __restrict__ desc,
+__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __restrict__ units,
+                                                               const HfxGroup* __restrict__ groups,
                                                                const float* __restrict__ ws,
+                                                               const float* __restrict__ ml, int Hq, int G,
                                                                __bf16* __restrict__ out) {
   constexpr int C4 = D / 4;                       // float4 columns of a row
   constexpr int Q = HFX_WG_THREADS / C4;          // threads per column: 8 (D = 128) or 16 (D = 64)
   __shared__ float s_max[Q];
   __shared__ float s_l[Q];
   __shared__ f32x4 s_acc[Q][C4];
-  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(desc);
-  const HfxUnit un = reinterpret_cast<const HfxUnit*>(desc + H->off_units)[blockIdx.x];
-  const HfxGroup gr = reinterpret_cast<const HfxGroup*>(desc + H->off_groups)[un.group];
-  const HfxReq rq = reinterpret_cast<const HfxReq*>(desc + H->off_req)[gr.req];
+  // everything the launch can know on the host comes in as an argument: unit -> group -> partials
+  // is the whole chain of dependent loads
+  const HfxUnit un = units[blockIdx.x];
+  const HfxGroup gr = groups[un.group];
   const int tid = threadIdx.x;
   const int col = tid % C4, q = tid / C4;
   const bool wide = gr.nsplit > 8;                // Q... only the first 8 thread rows are used below
@@ -98,9 +100,6 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __res
   const int sl = wide ? q : 0;
   const int row = wide ? un.chunk : un.chunk * 8 + q;
   const bool row_ok = q < 8 && row < gr.rows_per_split;
-  const int Hq = H->num_q_heads;
-  const int G = Hq / H->num_kv_heads;
-  const float* ml = reinterpret_cast<const float*>(reinterpret_cast<const char*>(ws) + H->ws_off_ml);
   const int rows = gr.rows_per_split, ns = gr.nsplit, base = gr.base_row;
   float mv[8], lv[8];
   float mloc = NEG_INF;
@@ -149,13 +148,13 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const char* __res
   if (!row_ok) return;
   long orow;
   if (gr.type == HFX_ITEM_DECODE) {
-    orow = (long)rq.q_start * Hq + gr.h0 * G + row;
+    orow = (long)gr.q_start * Hq + gr.h0 * G + row;
   } else {
     const int w = row / HFX_WAVE_ROWS, nn = row % HFX_WAVE_ROWS;
     const int head = gr.h0 + w % gr.hn;
     const int qrow = gr.row0 + (w / gr.hn) * HFX_WAVE_ROWS + nn;
-    if (qrow >= rq.q_len) return;
-    orow = ((long)rq.q_start + qrow) * Hq + head;
+    if (qrow >= gr.q_len) return;
+    orow = ((long)gr.q_start + qrow) * Hq + head;
   }
   const float inv = 1.0f / ll;
   bf16x4 ob;
@@ -881,9 +880,11 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
 // ----------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
-    const char* __restrict__ desc, int* __restrict__ ctrl, const __bf16* __restrict__ q,
+    const HfxHeader hdr, const char* __restrict__ desc, int* __restrict__ ctrl, const __bf16* __restrict__ q,
     const __bf16* __restrict__ pool, float* __restrict__ ws, __bf16* __restrict__ out) {
-  // the descriptor tables are read-only and distinct from everything written here, which lets
+  // The descriptor's header travels as a kernel argument (the host has it anyway), which takes one
+  // dependent load off the start of every workgroup.
+  // The descriptor tables are read-only and distinct from everything written here, which lets
   // the compiler fetch them with scalar loads that do not queue behind the KV stream
   KArgs a;
   a.desc = desc;
@@ -893,7 +894,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   a.out = out;
   __shared__ __attribute__((aligned(1024))) char smem[Smem<D>::kBytes];
   __shared__ int s_tk[2];
-  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(a.desc);
+  const HfxHeader* H = &hdr;
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const int n_items = H->n_items;
   Tickets t;
@@ -1015,23 +1016,28 @@ hipError_t max_resident_workgroups(int head_dim, int* per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, mixed_attention_kernel<64>, HFX_WG_THREADS, 0);
 }
 
-hipError_t launch_mixed_attention(int head_dim, int grid, int n_units, unsigned off_ctrl, void* desc, const void* q, const void* pool, void* ws, void* out,
-                                  hipStream_t stream) {
+hipError_t launch_mixed_attention(const HfxHeader& h, int grid, void* desc, const void* q, const void* pool, void* ws,
+                                  void* out, hipStream_t stream) {
+  const int head_dim = h.head_dim, n_units = h.n_units;
   const char* d = static_cast<const char*>(desc);
-  int* ctrl = reinterpret_cast<int*>(static_cast<char*>(desc) + off_ctrl);
+  int* ctrl = reinterpret_cast<int*>(static_cast<char*>(desc) + h.off_ctrl);
   const __bf16* qp = static_cast<const __bf16*>(q);
   const __bf16* pp = static_cast<const __bf16*>(pool);
   float* wp = static_cast<float*>(ws);
   __bf16* op = static_cast<__bf16*>(out);
   if (head_dim == 128)
-    hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
+    hipLaunchKernelGGL(mixed_attention_kernel<128>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, h, d, ctrl, qp, pp, wp, op);
   else
-    hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, d, ctrl, qp, pp, wp, op);
+    hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, h, d, ctrl, qp, pp, wp, op);
   if (n_units > 0) {
+    const HfxUnit* units = reinterpret_cast<const HfxUnit*>(d + h.off_units);
+    const HfxGroup* groups = reinterpret_cast<const HfxGroup*>(d + h.off_groups);
+    const float* ml = reinterpret_cast<const float*>(static_cast<const char*>(ws) + h.ws_off_ml);
+    const int Hq = h.num_q_heads, G = h.num_q_heads / h.num_kv_heads;
     if (head_dim == 128)
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
     else
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, d, wp, op);
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
   }
   return hipGetLastError();
 }

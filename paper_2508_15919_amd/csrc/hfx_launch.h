@@ -2,11 +2,13 @@
 #pragma once
 #include <hip/hip_runtime_api.h>
 
+#include "hfx_desc.h"
+
 namespace hfx {
 
 hipError_t max_resident_workgroups(int head_dim, int* per_cu);
-hipError_t launch_mixed_attention(int head_dim, int grid, int n_units, unsigned off_ctrl, void* desc, const void* q, const void* pool, void* ws, void* out,
-                                  hipStream_t stream);
+hipError_t launch_mixed_attention(const HfxHeader& header, int grid, void* desc, const void* q, const void* pool,
+                                  void* ws, void* out, hipStream_t stream);
 hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
                             void* v_out, hipStream_t stream);
 

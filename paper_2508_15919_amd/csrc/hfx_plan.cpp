@@ -119,7 +119,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
         int group = -1;
         if (nsplit > 1) {
           group = (int)P.groups.size();
-          HfxGroup gr = {nsplit, (int32_t)rows, ngc * G, HFX_ITEM_DECODE, r, g0, ngc, 0};
+          HfxGroup gr = {nsplit, (int32_t)rows, ngc * G, HFX_ITEM_DECODE, r, g0, ngc, 0, q.q_start, q.q_len};
           P.groups.push_back(gr);
         }
         for (int s = 0; s < nsplit; ++s) {
@@ -163,7 +163,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
             int group = -1;
             if (nsplit > 1) {
               group = (int)P.groups.size();
-              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_WAVE_ROWS, HFX_ITEM_PREFILL, r, g * G + hb * hpw, hpw, (int32_t)r0};
+              HfxGroup gr = {(int32_t)nsplit, (int32_t)rows, 4 * HFX_WAVE_ROWS, HFX_ITEM_PREFILL, r, g * G + hb * hpw, hpw, (int32_t)r0, q.q_start, q.q_len};
               P.groups.push_back(gr);
             }
             for (int64_t s = 0; s < nsplit; ++s) {
