@@ -298,9 +298,9 @@ class DescHeader(ctypes.Structure):
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
                                                "kb", "ke", "cost", "pad", "rq_kind", "rq_q_len", "rq_ctx_len",
-                                               "rq_q_start", "rq_bt_start", "rq_n_pages", "rq_pad0", "rq_pad1")])
+                                               "rq_q_start", "rq_bt_start", "rq_n_pages", "rq_bt_len", "rq_pad1")])
 REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
-                                              "pad0", "pad1")])
+                                              "bt_len", "pad1")])
 GROUP_DTYPE = np.dtype([(n, np.int32) for n in ("nsplit", "base_row", "rows_per_split", "type", "req", "h0", "hn",
                                                 "row0", "q_start", "q_len")])
 

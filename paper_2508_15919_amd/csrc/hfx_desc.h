@@ -4,11 +4,12 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 10u
+#define HFX_DESC_VERSION 11u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
 #define HFX_KEY_TILE 64          /* keys per prefill tile (4 pages) */
+#define HFX_BT_PAD 16            /* stored block-table entries after a request's last page, all naming that page */
 #define HFX_WAVE_ROWS 32         /* query rows one wavefront owns in a prefill item (one MFMA row block) */
 
 enum { HFX_ITEM_DECODE = 0, HFX_ITEM_PREFILL = 1 };
@@ -35,9 +36,12 @@ struct HfxHeader {
 struct HfxReq {
   int32_t kind, q_len, ctx_len;
   int32_t q_start;              /* first packed query row */
-  int32_t bt_start;             /* first entry in the stored block table */
-  int32_t n_pages;              /* ceil(ctx_len / 16) entries stored */
-  int32_t pad0, pad1;
+  int32_t bt_start;             /* first entry in the stored block table; a multiple of 4 */
+  int32_t n_pages;              /* ceil(ctx_len / 16) */
+  int32_t bt_len;               /* entries stored: n_pages rounded up to 4, plus HFX_BT_PAD; those past
+                                   n_pages repeat the last page, so that a tile's four ids can be fetched
+                                   as one aligned quad without clamping, a little way past the end */
+  int32_t pad1;
 };
 
 // One unit of work for one workgroup.

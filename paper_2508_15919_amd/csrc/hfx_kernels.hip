@@ -460,14 +460,17 @@ struct TilePages {
   int pg[4];
 };
 
-// bt: the step's whole stored block table; bt0: where the request's entries start
-__device__ __forceinline__ TilePages tile_pages(const int* __restrict__ bt, int bt0, int last_page, int kt) {
+// bt: the step's whole stored block table; bt0: where the request's entries start (a multiple
+// of 4); kt: first key of the tile (a multiple of 64).  The stored table repeats the last page for
+// HFX_BT_PAD entries behind each request, so the quad needs no clamping up to three tiles past the end.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ TilePages tile_pages(const int* __restrict__ bt, int bt0, int kt) {
+  const i32x4 v = *reinterpret_cast<const i32x4*>(bt + bt0 + kt / HFX_PAGE);
   TilePages t;
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int lp = kt / HFX_PAGE + s;
-    t.pg[s] = bt[bt0 + (lp < last_page ? lp : last_page)];
-  }
+  t.pg[0] = v[0];
+  t.pg[1] = v[1];
+  t.pg[2] = v[2];
+  t.pg[3] = v[3];
   return t;
 }
 
@@ -630,11 +633,10 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
 // and, when the next item of this workgroup is a prefill item too, that one.
 struct TileStream {
   int bt0;            // start of the current item's request in the stored block table
-  int last_page;
   int g;              // kv-head
   int end;            // first key past the current item's last (whole) tile
   bool next_ok;
-  int bt0_n, last_n, g_n, kb_n;   // the same for the next item, and its first key
+  int bt0_n, g_n, kb_n;   // the same for the next item, and its first key
 };
 
 // Pages of the 64-key tile that starts `kt` keys into the stream (kt counts on past the end of
@@ -644,10 +646,9 @@ __device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, co
                                                   int& g_out) {
   const bool into_next = kt >= ts.end && ts.next_ok;
   const int bt0 = into_next ? ts.bt0_n : ts.bt0;
-  const int lp = into_next ? ts.last_n : ts.last_page;
   const int k = into_next ? ts.kb_n + (kt - ts.end) : kt;
   g_out = into_next ? ts.g_n : ts.g;
-  return tile_pages(bt, bt0, lp, k);
+  return tile_pages(bt, bt0, k);
 }
 
 // One 64-key tile from the LDS buffer `kcur`.  Order of the memory traffic: the V fragments of
@@ -660,7 +661,8 @@ __device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, co
 // have arrived, the K tile requested one tile earlier has landed too, so the barrier at the end
 // needs no wait of its own.
 template <int D>
-__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, VHalf<D>& vx, VHalf<D>& vy,
+__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, TilePages& tn, int& gn, VHalf<D>& vx,
+                                             VHalf<D>& vy,
                                              const char* kcur, char* kfill, const __bf16* pool,
                                              const int* __restrict__ bt, const TileStream& ts, int kt, int wave_kend, int wave_pmin,
                                              int ctx_len, int Hkv, int k_lane, int v_lane, int j, float sl2,
@@ -668,8 +670,8 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
   const bool active = kt < wave_kend;
   const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
   const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
-  // Every load below is issued unconditionally (past the end of the stream the page indices are
-  // clamped, so the addresses stay valid and the data is simply not used): the wait counters the
+  // Every load below is issued unconditionally (past the end of the stream the stored block table
+  // repeats the request's last page, so the addresses stay valid and the data is simply not used): the wait counters the
   // compiler derives are compile-time constants, and a path that skipped a load would force
   // them to zero and stall the pipeline on every tile.
   KFrags<D> kf;
@@ -677,13 +679,13 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, V
   k_frags_read<D>(kf, kcur + k_lane);
   if (active) prefill_half<D>(w, vx, kf, masked, past_ctx, kt, ctx_len, j, sl2);
   k_frags_read<D>(kf, kcur + 1024 + k_lane);
-  int g1, g2;
-  tp = stream_pages(bt, ts, kt + HFX_KEY_TILE, g1);
-  v_half_load<D>(vx, pool, tp.pg[0], tp.pg[1], Hkv, g1, v_lane);
+  // tn, gn: pages and kv-head of the stream's next tile, looked up one tile ago
+  v_half_load<D>(vx, pool, tn.pg[0], tn.pg[1], Hkv, gn, v_lane);
+  tp = tn;
   // The copy goes last: the compiler does not count it, so the waits it derives for the V
   // fragments above would otherwise also wait for a copy issued in front of them.
-  const TilePages ahead = stream_pages(bt, ts, kt + 2 * HFX_KEY_TILE, g2);
-  k_tile_async<D>(kfill, pool, ahead, Hkv, g2, wave, lane);
+  tn = stream_pages(bt, ts, kt + 2 * HFX_KEY_TILE, gn);
+  k_tile_async<D>(kfill, pool, tn, Hkv, gn, wave, lane);
   // on the diagonal the second 32 keys may lie past every row of the wavefront
   if (kt + 32 < wave_kend) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
   else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
@@ -795,12 +797,10 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   TileStream ts;
   auto set_stream = [&]() {
     ts.bt0 = it.rq.bt_start;
-    ts.last_page = it.rq.n_pages - 1;
     ts.g = it.h0 / G;
     ts.end = it.kb + (it.ke - it.kb + HFX_KEY_TILE - 1) / HFX_KEY_TILE * HFX_KEY_TILE;
     ts.next_ok = t.nxt < n_items && nx.type == HFX_ITEM_PREFILL;
     ts.bt0_n = nx.rq.bt_start;
-    ts.last_n = nx.rq.n_pages - 1;
     ts.g_n = nx.h0 / G;
     ts.kb_n = nx.kb;
   };
@@ -818,13 +818,11 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
 
   // cold start: the first two tiles of the stream and the first V fragments
   int kt = it.kb;
-  TilePages tp = tile_pages(bt_all, ts.bt0, ts.last_page, kt);
+  TilePages tp = tile_pages(bt_all, ts.bt0, kt);
   k_tile_async<D>(smem, a.pool, tp, Hkv, ts.g, wave, lane);
-  {
-    int g1;
-    const TilePages t1 = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, g1);
-    k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, t1, Hkv, g1, wave, lane);
-  }
+  int gn;
+  TilePages tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
+  k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, tn, Hkv, gn, wave, lane);
   VHalf<D> vx, vy;
   v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, ts.g, v_lane);
   HFX_WAIT_VMCNT(0);
@@ -834,7 +832,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   for (;;) {
     int fill = cur + 2 * Smem<D>::kKBytes;
     if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
-    prefill_tile<D>(w, tp, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
+    prefill_tile<D>(w, tp, tn, gn, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
                     it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane, kt == it.kb, t, s_tk);
     cur += Smem<D>::kKBytes;
     if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
@@ -861,11 +859,10 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     if (kt + HFX_KEY_TILE >= it.ke) {
       // a one-tile item: the stream position after it belongs to an item that was not known yet
       // when that position's copy was issued; request it again, now with the right pages
-      int g1;
       int nb = cur + Smem<D>::kKBytes;
       if (nb >= 3 * Smem<D>::kKBytes) nb = 0;
-      const TilePages t1 = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, g1);
-      k_tile_async<D>(smem + nb, a.pool, t1, Hkv, g1, wave, lane);
+      tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
+      k_tile_async<D>(smem + nb, a.pool, tn, Hkv, gn, wave, lane);
     }
   }
   HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the stream

@@ -79,11 +79,12 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     q.q_len = q_len[r];
     q.ctx_len = ctx_len[r];
     q.n_pages = (int32_t)(((int64_t)ctx_len[r] + HFX_PAGE - 1) / HFX_PAGE);
-    if (T > 0x7fffffff - q_len[r] || nbt > 0x7fffffff - q.n_pages) return HFX_ERR_LEN;
+    q.bt_len = ((q.n_pages + 3) & ~3) + HFX_BT_PAD;
+    if (T > 0x7fffffff - q_len[r] || nbt > 0x7fffffff - q.bt_len) return HFX_ERR_LEN;
     q.q_start = (int32_t)T;
     q.bt_start = (int32_t)nbt;
     T += q_len[r];
-    nbt += q.n_pages;
+    nbt += q.bt_len;
     if (kind[r] == HFX_DECODE) {
       total_ns += (double)ctx_len[r] * Hkv * D * 4.0 / kDecodeBytesPerNs;
     } else {
@@ -307,8 +308,12 @@ hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, 
   put(h.off_ctrl, nullptr, 0, h.off_req);
   put(h.off_req, P.reqs.data(), sizeof(HfxReq) * P.reqs.size(), h.off_bt);
   int32_t* bt = (int32_t*)(base + h.off_bt);
-  for (int r = 0; r < R; ++r)
-    std::memcpy(bt + P.reqs[(size_t)r].bt_start, bt_pages + bt_indptr[r], 4ull * (size_t)P.reqs[(size_t)r].n_pages);
+  for (int r = 0; r < R; ++r) {
+    const HfxReq& q = P.reqs[(size_t)r];
+    int32_t* dst = bt + q.bt_start;
+    std::memcpy(dst, bt_pages + bt_indptr[r], 4ull * (size_t)q.n_pages);
+    for (int i = q.n_pages; i < q.bt_len; ++i) dst[i] = dst[q.n_pages - 1];
+  }
   put(h.off_bt + 4ull * (uint64_t)P.n_bt, nullptr, 0, h.off_items);
   put(h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size(), h.off_groups);
   put(h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size(), h.off_units);

@@ -67,6 +67,10 @@ def check_coverage(b, d):
         assert n == (int(b.ctx_len[r]) + 15) // 16
         assert np.array_equal(d["bt"][reqs["bt_start"][r]:reqs["bt_start"][r] + n],
                               b.bt_pages[b.bt_indptr[r]:b.bt_indptr[r] + n])
+        # stored quad-aligned, with the last page repeated behind it
+        m = int(reqs["bt_len"][r])
+        assert reqs["bt_start"][r] % 4 == 0 and m == (n + 3) // 4 * 4 + 16
+        assert np.all(d["bt"][reqs["bt_start"][r] + n:reqs["bt_start"][r] + m] == b.bt_pages[b.bt_indptr[r] + n - 1])
     qi = b.q_indptr()
     assert np.array_equal(reqs["q_start"], qi[:-1])
     slot_owner = np.zeros(max(1, h.n_partial_rows), np.int32)
@@ -96,7 +100,7 @@ def check_coverage(b, d):
                 assert it["cost"] == int(4.0 * b.head_dim * it["hn"] * pairs / 2000.0 + 3000.0)
             visible = (np.arange(c)[None, :] <= (p + np.arange(ql))[:, None])
             assert np.all(cover[:, visible] == 1), "every visible pair exactly once"
-        for f in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages"):
+        for f in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages", "bt_len"):
             assert np.all(mine["rq_" + f] == reqs[f][r]), "an item carries a copy of its request record"
         for it in mine:
             if it["group"] >= 0:
@@ -209,7 +213,7 @@ def test_validation_errors(lib):
 def test_extra_reserved_pages_are_ignored(lib):
     b = synth.make_batch(4, 2, 64, [DECODE, PREFILL], [1, 20], [37, 50], 3, extra_pages_per_request=3)
     d = fill(b)
-    assert d["header"].n_bt == 3 + 4
+    assert d["header"].n_bt == (4 + 16) + (4 + 16)      # stored: rounded up to 4 entries, plus the padding
     check_coverage(b, d)
 
 
