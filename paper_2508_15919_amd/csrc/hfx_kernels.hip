@@ -480,27 +480,38 @@ __device__ __forceinline__ TilePages tile_pages(const int* __restrict__ bt, int 
 template <int D>
 __device__ __forceinline__ void k_tile_async(char* kbuf, const __bf16* pool, const TilePages& tp, int Hkv, int g,
                                              int wave, int lane) {
-  constexpr int kPerWave = (D / 16) * 2 / 4;
+  constexpr int kPerWave = (D / 16) * 2 / 4;       // 4 (D = 128) or 2 (D = 64) copies per wavefront
   constexpr long kBlock = 16 * D;
+  // A wavefront's copies are q = wave * kPerWave + i: dimension group kk = q >> 1, key half kh = q & 1.
+  // The K-block addresses of the tile's four pages are formed in scalar registers; a lane then only
+  // picks the page of its key (lanes 16-31 and 48-63 hold the second page of a half) and adds its
+  // own offset; copies that differ only in kk use the instruction's immediate offset.
+  auto k_block = [&](int pg) { return reinterpret_cast<uintptr_t>(pool + (((long)pg * Hkv + g) * 2) * kBlock); };
+  const bool second = (lane >> 4) & 1;
+  const int kk0 = (wave * kPerWave) >> 1;
+  // lane l fills LDS slot l of the 1 KB block: slot = 32 * (dimension half) + key, so that the 16
+  // lanes the LDS serves together later read 16 different bank groups
+  const unsigned lane_bytes = (unsigned)(((kk0 * 16 + (lane & 15)) * 16 + (lane >> 5) * 8) * 2);
 #pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int q = wave * kPerWave + i;
-    const int kk = q >> 1, kh = q & 1;
-    const int pg_lo = kh ? tp.pg[2] : tp.pg[0], pg_hi = kh ? tp.pg[3] : tp.pg[1];
-    // lane l fills LDS slot l of the 1 KB block: slot = 32 * (dimension half) + key, so that the 16
-    // lanes the LDS serves together later read 16 different bank groups
-    const int pg = ((lane >> 4) & 1) ? pg_hi : pg_lo;
-    const __bf16* src = pool + (((long)pg * Hkv + g) * 2) * kBlock + (kk * 16 + (lane & 15)) * 16 + (lane >> 5) * 8;
-    char* dst = kbuf + kk * (HFX_KEY_TILE * 32) + kh * 1024;
-    // Issued as inline assembly on purpose: the compiler's wait-count pass treats its own
-    // direct-to-LDS intrinsic as aliasing every later LDS read and drains the whole vector-memory
-    // queue in front of them, which would stall the V stream on every tile.  Here the copy is
-    // ordered by hand: the caller waits for vmcnt(0) and crosses a barrier before the tile is read.
-    const unsigned lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)dst;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(src), "s"(lds)
-                 : "m0", "memory");
+  for (int kh = 0; kh < 2; ++kh) {
+    const uintptr_t first_page = k_block(kh ? tp.pg[2] : tp.pg[0]), second_page = k_block(kh ? tp.pg[3] : tp.pg[1]);
+    const char* src = reinterpret_cast<const char*>((second ? second_page : first_page) + lane_bytes);
+#pragma unroll
+    for (int dk = 0; dk < kPerWave / 2; ++dk) {
+      char* dst = kbuf + (kk0 + dk) * (HFX_KEY_TILE * 32) + kh * 1024;
+      // Issued as inline assembly on purpose: the compiler's wait-count pass treats its own
+      // direct-to-LDS intrinsic as aliasing every later LDS read and drains the whole vector-memory
+      // queue in front of them, which would stall the V stream on every tile.  Here the copy is
+      // ordered by hand: the caller waits for vmcnt(0) and crosses a barrier before the tile is read.
+      const unsigned lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)dst;
+      if (dk == 0)
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "m0", "memory");
+      else   // the immediate offset moves the LDS address along with the global one: take it off again
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:512"
+                     :
+                     : "v"(src), "s"(lds - 512u)
+                     : "m0", "memory");
+    }
   }
 }
 
