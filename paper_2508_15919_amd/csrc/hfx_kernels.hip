@@ -446,8 +446,8 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
 // load of a 1 KB MFMA operand costs about 16 cycles of its unit per CU, an MFMA 32x32x16 takes
 // 32 cycles of one of four SIMDs), so the two contractions take their tiles over two paths:
 //   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows from an LDS tile that the workgroup fills
-//                                                 once per 64 keys with direct-to-LDS loads (double
-//                                                 buffered; the page's K block is already in operand
+//                                                 once per 64 keys with direct-to-LDS loads (three
+//                                                 buffers; the page's K block is already in operand
 //                                                 order), B = Q^T in registers;
 //   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows loaded straight from the page pool (a
 //                                                 dimension-major V block is the operand layout),
@@ -651,8 +651,8 @@ struct TileStream {
 };
 
 // Pages of the 64-key tile that starts `kt` keys into the stream (kt counts on past the end of
-// the current item into the next one's range; with no next prefill item the indices are clamped
-// into the current request and the data is never used).
+// the current item into the next one's range; with no next prefill item it reads on in the
+// current request's stored table, whose padding repeats the last page, and the data is never used).
 __device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, const TileStream& ts, int kt,
                                                   int& g_out) {
   const bool into_next = kt >= ts.end && ts.next_ok;
