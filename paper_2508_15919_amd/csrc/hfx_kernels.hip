@@ -860,6 +860,10 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     set_stream();
     wr = wave_rows<D>(it, wave, n);
     q_load<D>(w, a, it, wr, Hq, j);
+    // Q is needed by the very next MFMA.  Waiting for it here, in so many words, also tells the
+    // compiler that nothing is in flight when the tile loop is re-entered; left to itself it
+    // carries the Q loads into the loop as pending and drains the queue down to them on every tile.
+    HFX_WAIT_VMCNT(0);
 #pragma unroll
     for (int b = 0; b < D / 32; ++b)
 #pragma unroll
