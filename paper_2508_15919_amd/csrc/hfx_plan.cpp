@@ -69,7 +69,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   P.items.clear();
   P.groups.clear();
   int64_t T = 0, nbt = 0;
-  double total_ns = 0.0;
+  double dec_ns = 0.0, pre_ns = 0.0;   // modelled time of each kind of work
   for (int r = 0; r < R; ++r) {
     if (kind[r] != HFX_DECODE && kind[r] != HFX_PREFILL) return HFX_ERR_KIND;
     if (q_len[r] < 1 || ctx_len[r] < q_len[r]) return HFX_ERR_LEN;
@@ -86,14 +86,15 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     T += q_len[r];
     nbt += q.bt_len;
     if (kind[r] == HFX_DECODE) {
-      total_ns += (double)ctx_len[r] * Hkv * D * 4.0 / kDecodeBytesPerNs;
+      dec_ns += (double)ctx_len[r] * Hkv * D * 4.0 / kDecodeBytesPerNs;
     } else {
       double ql = q_len[r], p = ctx_len[r] - q_len[r];
-      total_ns += 4.0 * D * Hq * (ql * p + ql * (ql + 1) / 2) / kPrefillFlopsPerNs;
+      pre_ns += 4.0 * D * Hq * (ql * p + ql * (ql + 1) / 2) / kPrefillFlopsPerNs;
     }
   }
   P.total_q = (int32_t)T;
   P.n_bt = (int32_t)nbt;
+  const double total_ns = dec_ns + pre_ns;
   const double cap_ns = std::max(total_ns / (HFX_PLAN_WGS * kDecodeItemsPerWg), kMinItemNs);
   const double cap_prefill_ns = std::max(total_ns / (HFX_PLAN_WGS * kPrefillItemsPerWg), kMinItemNs);
 
@@ -192,7 +193,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   }
   P.n_partial_rows = (int32_t)rows;
   // queue order: descending cost, ties in creation order: a stable radix sort (11-bit digits) of
-  // (inverted cost, index) keys, then one permutation of the 80-byte items.
+  // (inverted cost, index) keys, then one permutation of the item records.
   {
     const size_t n = P.items.size();
     std::vector<uint64_t>& key = P.sort_keys;
@@ -219,7 +220,31 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     }
     std::vector<HfxItem>& sorted = P.sort_tmp;
     sorted.resize(n);
-    for (size_t i = 0; i < n; ++i) sorted[i] = P.items[(size_t)(a[i] & 0xffffffffu)];
+    if (dec_ns > pre_ns && pre_ns > 0.0) {
+      // A step whose decode work outweighs its prefill work: the two kinds alternate in blocks of half
+      // the planning width, decode first, each kind in descending cost.  With the first items dealt
+      // out by workgroup index, the lower half of the workgroups then starts on decode items and the
+      // upper half on prefill items, which puts one of each on every CU: the matrix work runs in
+      // the shadow of the memory-bound stream for as long as it lasts (measured on the Llama-8B-shaped
+      // mixed step: 5 % less time than plain descending order; on prefill-dominated steps the same
+      // interleave costs 2-13 %, so they keep the plain order).
+      constexpr size_t kBlockItems = HFX_PLAN_WGS / 2;
+      std::vector<uint32_t>& dec = P.order_dec;
+      std::vector<uint32_t>& pre = P.order_pre;
+      dec.clear();
+      pre.clear();
+      for (size_t i = 0; i < n; ++i) {
+        const uint32_t idx = (uint32_t)(a[i] & 0xffffffffu);
+        (P.items[idx].type == HFX_ITEM_DECODE ? dec : pre).push_back(idx);
+      }
+      size_t di = 0, pi = 0, o = 0;
+      while (di < dec.size() || pi < pre.size()) {
+        for (size_t k = 0; k < kBlockItems && di < dec.size(); ++k) sorted[o++] = P.items[dec[di++]];
+        for (size_t k = 0; k < kBlockItems && pi < pre.size(); ++k) sorted[o++] = P.items[pre[pi++]];
+      }
+    } else {
+      for (size_t i = 0; i < n; ++i) sorted[i] = P.items[(size_t)(a[i] & 0xffffffffu)];
+    }
     P.items.swap(sorted);
   }
   // merge work units: groups with many splits get 8 threads per (row, column) and one row per

@@ -19,6 +19,7 @@ struct Plan {
   std::vector<uint64_t> sort_keys;
   std::vector<HfxItem> sort_tmp;
   std::vector<int32_t> split_cost;
+  std::vector<uint32_t> order_dec, order_pre;
 };
 
 hfx_status check_shape(const hfx_shape* shape);

@@ -59,7 +59,20 @@ def check_coverage(b, d):
     Hq, Hkv = b.num_q_heads, b.num_kv_heads
     G = Hq // Hkv
     assert h.n_items == len(items) == h.n_decode_items + h.n_prefill_items
-    assert np.all(np.diff(items["cost"]) <= 0), "queue must be in descending modelled cost"
+    for ty in (0, 1):
+        assert np.all(np.diff(items["cost"][items["type"] == ty]) <= 0), "each kind in descending modelled cost"
+    pre_first = np.nonzero(items["type"] == 1)[0]
+    if len(pre_first) == 0 or len(pre_first) == len(items) or np.all(np.diff(items["cost"]) <= 0):
+        pass                                   # one kind only, or plain descending order
+    else:
+        # decode-dominated mixed step: blocks of 256, decode first, as long as both kinds last
+        ty = items["type"]
+        n_dec, n_pre = int((ty == 0).sum()), int((ty == 1).sum())
+        want = []
+        while n_dec or n_pre:
+            k = min(256, n_dec); want += [0] * k; n_dec -= k
+            k = min(256, n_pre); want += [1] * k; n_pre -= k
+        assert ty.tolist() == want
     assert np.all(d["ctrl"] == 0)
     # stored block table: exactly the needed pages, in order
     for r in range(b.num_requests):
