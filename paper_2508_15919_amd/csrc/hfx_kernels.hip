@@ -528,7 +528,12 @@ __device__ __forceinline__ void v_half_load(VHalf<D>& vh, const __bf16* pool, in
   constexpr long kBlock = 16 * D;
 #pragma unroll
   for (int sp = 0; sp < 2; ++sp) {
-    const __bf16* vb = pool + (((long)(sp ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock + v_lane;
+    // The V block starts 4096 bytes into the (page, kv-head) block, one more than a load's immediate
+    // offset can hold.  Left visible, the compiler peels that constant off the scalar block address
+    // and adds it back per lane, twice; the empty asm keeps the scalar sum in one piece.
+    long block = (((long)(sp ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock;
+    asm volatile("" : "+s"(block));
+    const __bf16* vb = pool + block + v_lane;
 #pragma unroll
     for (int b = 0; b < D / 32; ++b) vh.f[sp][b] = ld16(vb + b * 512);
   }
