@@ -15,11 +15,11 @@ namespace hfx {
 // order the queue and size the splits.
 static const double kDecodeBytesPerNs = 12.0;
 static const double kPrefillFlopsPerNs = 2000.0;
-static const double kMinItemNs = 16000.0;
+static const double kMinItemNs = 32000.0;
 static const int kMinDecodeTokens = 128;
 static const int kMinPrefillKeys = 256;
 static const int kMaxSplits = 64;
-static const int kDecodeItemsPerWg = 8;    // decode partials are small (rows of D + 2 floats per q-head)
+static const int kDecodeItemsPerWg = 4;    // decode partials are small (rows of D + 2 floats per q-head)
 static const int kPrefillItemsPerWg = 2;   // prefill partials are 128 rows: split only where balance needs it
 
 static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
@@ -95,7 +95,9 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   P.total_q = (int32_t)T;
   P.n_bt = (int32_t)nbt;
   const double total_ns = dec_ns + pre_ns;
-  const double cap_ns = std::max(total_ns / (HFX_PLAN_WGS * kDecodeItemsPerWg), kMinItemNs);
+  // decode pieces are sized against the decode work alone: in a step dominated by prefill they stay
+  // small and fill the gaps between the large prefill items
+  const double cap_ns = std::max(dec_ns / (HFX_PLAN_WGS * kDecodeItemsPerWg), kMinItemNs);
   const double cap_prefill_ns = std::max(total_ns / (HFX_PLAN_WGS * kPrefillItemsPerWg), kMinItemNs);
 
   int64_t rows = 0;
