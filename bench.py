@@ -101,6 +101,14 @@ def path_figures(torch, hb, batch, pools, iters, warmup):
         fl = batch.prefill_flops()
         out.update(bound="mfma", algorithmic_flops=fl, achieved_TFLOPs=round(fl / avg / 1e9, 1),
                    frac_of_bf16_mfma_peak=round(fl / avg / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4))
+        # the same peak from what the device reports: CUs x 4096 bf16 flop/clk/CU x its maximum clock
+        props = torch.cuda.get_device_properties(0)
+        clock_khz = getattr(props, "clock_rate", 0)
+        if clock_khz:
+            peak = props.multi_processor_count * 4096 * clock_khz * 1e3 / 1e12
+            out.update(device_cus=props.multi_processor_count, device_clock_mhz=round(clock_khz / 1e3),
+                       peak_TFLOPs_at_device_clock=round(peak, 1),
+                       frac_of_peak_at_device_clock=round(fl / avg / 1e9 / peak, 4))
     else:
         byt = batch.decode_io_bytes() + batch.prefill_io_bytes()
         out.update(algorithmic_bytes=byt, achieved_GBs=round(byt / avg / 1e6, 1),
@@ -301,6 +309,8 @@ def main() -> int:
             td, tp = paths["cfg2_decode_only"]["launch_ms_avg"], paths["cfg2_prefill_only"]["launch_ms_avg"]
             paths["cfg2_mixed_vs_parts"] = {"mixed_ms": round(launch_avg, 4), "max_of_parts_ms": round(max(td, tp), 4),
                                             "sum_of_parts_ms": round(td + tp, 4)}
+        # the same step with one pool only: consecutive launches find most of their KV in the last-level cache
+        leg("cfg2_warm_single_pool", lambda: path_figures(torch, hb, b, pools[:1], 100, 10))
         leg("cfg2_kv_append", lambda: append_figures(torch, hb, b, pools[0], 100, 10))
         if len(pools) > 1:      # the pools are copies of each other, so the move leaves their contents as they are
             leg("cfg2_page_copy", lambda: copy_figures(torch, hb, b, pools[0], pools[1], 50, 5))
@@ -308,11 +318,11 @@ def main() -> int:
         pools.clear()
         torch.cuda.empty_cache()
 
-        def big(which):
+        def big(which, part=None):
             bb = synth.config(which, fill_pool=False)
-            if which == 4:
-                bb = bb.sub_batch(synth.PREFILL)
-            pp = device_pool(torch, bb, 1000 + which, copies=1 if which == 3 else 2)
+            if part is not None:
+                bb = bb.sub_batch(part)
+            pp = device_pool(torch, bb, 1000 + which, copies=1 if bb.num_pages * bb.num_kv_heads > (1 << 19) else 2)
             try:
                 return path_figures(torch, hb, bb, pp, 30, 5)
             finally:
@@ -320,7 +330,10 @@ def main() -> int:
                 torch.cuda.empty_cache()
 
         leg("decode_heavy", lambda: big(3))
-        leg("prefill_heavy", lambda: big(4))
+        leg("prefill_heavy", lambda: big(4, synth.PREFILL))
+        # the long-context tensor-parallel share (8 q-heads on 1 kv-head), its two halves
+        leg("cfg5_decode_part", lambda: big(5, synth.DECODE))
+        leg("cfg5_prefill_part", lambda: big(5, synth.PREFILL))
 
         def short_context():
             bb = synth.table1_short_context(seed=7, requests_per_task=64)
