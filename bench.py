@@ -101,14 +101,6 @@ def path_figures(torch, hb, batch, pools, iters, warmup):
         fl = batch.prefill_flops()
         out.update(bound="mfma", algorithmic_flops=fl, achieved_TFLOPs=round(fl / avg / 1e9, 1),
                    frac_of_bf16_mfma_peak=round(fl / avg / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4))
-        # the same peak from what the device reports: CUs x 4096 bf16 flop/clk/CU x its maximum clock
-        props = torch.cuda.get_device_properties(0)
-        clock_khz = getattr(props, "clock_rate", 0)
-        if clock_khz:
-            peak = props.multi_processor_count * 4096 * clock_khz * 1e3 / 1e12
-            out.update(device_cus=props.multi_processor_count, device_clock_mhz=round(clock_khz / 1e3),
-                       peak_TFLOPs_at_device_clock=round(peak, 1),
-                       frac_of_peak_at_device_clock=round(fl / avg / 1e9 / peak, 4))
     else:
         byt = batch.decode_io_bytes() + batch.prefill_io_bytes()
         out.update(algorithmic_bytes=byt, achieved_GBs=round(byt / avg / 1e6, 1),
