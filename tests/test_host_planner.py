@@ -250,3 +250,17 @@ def test_copy_pages_validation(lib):
         with pytest.raises(hb.HfxError) as e:
             call(s_ids, d_ids, **kw)
         assert e.value.code == code, (s_ids, d_ids, kw)
+
+
+def test_header_is_plain_c_and_cpp(tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "hfxattn.h")
+    for compiler, flags, ext in (("gcc", ["-std=c99", "-pedantic", "-Wall", "-Werror"], "c"),
+                                 ("g++", ["-std=c++11", "-Wall", "-Werror"], "cpp")):
+        if shutil.which(compiler) is None:
+            pytest.skip(f"{compiler} not available")
+        src = tmp_path / f"use.{ext}"
+        src.write_text('#include "hfxattn.h"\nint main(void) { hfx_shape s; hfx_decision d; (void)s; (void)d; return HFX_OK; }\n')
+        subprocess.run([compiler, *flags, "-fsyntax-only", "-I", os.path.dirname(hdr), str(src)], check=True)
