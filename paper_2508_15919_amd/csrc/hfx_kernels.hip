@@ -750,24 +750,46 @@ __device__ __forceinline__ void q_load(PrefillWave<D>& w, const KArgs& a, const 
 }
 
 // Result of a finished item: normalised bf16 rows, or (m, l, acc) partial rows when the item is one split of a group.
+// A lane holds 4-dimension pieces of its own row, so stored straight from the registers every
+// instruction would touch 32 rows with 16 bytes each, and the write path takes one request per
+// (instruction, line): measured, the 16 stores of an item took longer to issue than two of its
+// tiles took to compute.  The bf16 rows therefore go through `stage` (4 KB of LDS owned by this
+// wavefront, 64 dimensions of its 32 rows at a time) and leave as whole 128-byte lines, 8 rows per
+// instruction.  The 8-byte pieces of a row are swizzled by the row number to spread the LDS banks.
 template <int D>
 __device__ __forceinline__ void prefill_store(const KArgs& a, const HfxHeader* H, const HfxItem& it, const WaveRows& r,
-                                              const PrefillWave<D>& w, int Hq, int wave, int n, int j) {
+                                              const PrefillWave<D>& w, int Hq, int wave, int lane, char* stage) {
   // o[b][v] is dimension 32b + (v>>2)*8 + 4j + (v&3) of chunk row `qrow`
   const float lsum = sum_xor32(w.l);
+  // The lane's parts of the destination addresses are formed here, per call: left visible, the
+  // compiler hoists them out of the item loop, runs out of registers and parks them in scratch
+  // memory, and the reload at every hand-over waits for every load the tile stream has in flight.
+  asm volatile("" : "+v"(lane));
+  const int n = lane & 31, j = lane >> 5;
   if (it.group < 0) {
-    if (r.store) {
-      const float inv = 1.0f / lsum;
-      __bf16* dst = a.out + (((long)it.rq.q_start + r.qrow) * Hq + r.head) * D + 4 * j;
+    const float inv = 1.0f / lsum;
+    const int row0 = r.qrow - n;                 // first chunk row of this wavefront
+    const int rr = lane >> 3, u = lane & 7;      // read-back: row rr + 8i, 16-byte piece u
+    __bf16* dst = a.out + (((long)it.rq.q_start + row0 + rr) * Hq + r.head) * D + u * 8;
 #pragma unroll
-      for (int b = 0; b < D / 32; ++b)
+    for (int p = 0; p < D / 64; ++p) {
+#pragma unroll
+      for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           bf16x4 ob;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(w.o[b][q4 * 4 + e] * inv);
-          *reinterpret_cast<bf16x4*>(dst + b * 32 + q4 * 8) = ob;
+          for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(w.o[2 * p + bb][q4 * 4 + e] * inv);
+          const int c = 8 * bb + 2 * q4 + j;     // 8-byte piece of the 128-byte half row
+          *reinterpret_cast<bf16x4*>(stage + n * 128 + ((c ^ ((n & 7) << 1)) * 8)) = ob;
         }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = rr + 8 * i;
+        const bf16x8 line = *reinterpret_cast<const bf16x8*>(stage + row * 128 + ((u ^ (row & 7)) * 16));
+        if (row0 + row < it.rq.q_len)
+          *reinterpret_cast<bf16x8*>(dst + (long)i * 8 * Hq * D + p * 64) = line;
+      }
     }
   } else {
     float* ws_acc = a.ws;
@@ -794,13 +816,14 @@ __device__ __forceinline__ void prefill_store(const KArgs& a, const HfxHeader* H
 // Returns with t.cur at the first item it did not process.
 template <int D>
 __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* __restrict__ items, int n_items,
-                            Tickets& t, int* s_tk, int* ctrl, char* smem) {
+                            Tickets& t, int* s_tk, int* ctrl, char* smem, char* o_stage) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
   const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
   const int G = Hq / Hkv;
   const int n = lane & 31, j = lane >> 5;
+  char* stage = o_stage + wave * 4096;
   const float sl2 = H->softmax_scale * 1.4426950408889634f;
   const int* bt_all = reinterpret_cast<const int*>(a.desc + H->off_bt);
   // row of this lane's key inside a 32-key half of the LDS tile
@@ -857,7 +880,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
 
     // hand-over: the item is finished; its successor's first tiles are already on their way
     const bool carry_on = ts.next_ok;
-    prefill_store<D>(a, H, it, wr, w, Hq, wave, n, j);
+    prefill_store<D>(a, H, it, wr, w, Hq, wave, lane, stage);
     tickets_take(t, s_tk, ctrl);
     if (!carry_on) break;
     it = nx;
@@ -911,6 +934,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   a.out = out;
   __shared__ __attribute__((aligned(1024))) char smem[Smem<D>::kBytes];
   __shared__ int s_tk[2];
+  __shared__ __attribute__((aligned(128))) char s_ostage[4 * 4096];   // result rows on their way out (prefill_store)
   const HfxHeader* H = &hdr;
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const int n_items = H->n_items;
@@ -923,7 +947,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
     if (items[t.cur].type == HFX_ITEM_DECODE) {
       decode_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem);
     } else {
-      prefill_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem);
+      prefill_run<D>(a, H, items, n_items, t, s_tk, &ctrl[0], smem, s_ostage);
     }
   }
   // the ticket fetched last is never used; it must have reached the counter before this
