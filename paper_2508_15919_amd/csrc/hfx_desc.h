@@ -23,7 +23,7 @@ struct HfxHeader {
   int32_t n_partial_rows;       /* workspace rows: one (query row, q-head) partial each */
   int32_t n_bt;                 /* page ids stored */
   uint32_t off_ctrl, off_req, off_bt, off_items, off_groups;
-  uint32_t n_ctrl;              /* control words: [0] tickets handed out past the statically dealt first three per workgroup, [1] finished workgroups */
+  uint32_t n_ctrl;              /* control words: [0] tickets handed out past the two dealt to each workgroup by index, [1] finished workgroups */
   uint64_t total_bytes;
   uint64_t workspace_bytes;
   uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */

@@ -173,36 +173,36 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __
 // result layout, each lane ends up holding 8 consecutive tokens of one page -- exactly the
 // 16 bytes of a dimension-major V row that the second contraction needs, with no shuffles.
 // ----------------------------------------------------------------------------------------------
-// Work-queue tickets of a workgroup.  It holds the item it is processing, the item after it
+// Work-queue tickets of a workgroup.  It holds the item it is processing and the item after it
 // (whose record is therefore known while the current item runs, so that a prefill item can
-// request the first tiles of its successor before it ends) and, in thread 0, the ticket after
-// that, fetched at the previous hand-over.  The first three tickets of a workgroup are its
-// index plus 0, 1 and 2 grids (the queue is in descending cost, so this deals the largest items
-// out evenly); later ones come from the atomic counter.
+// request the first tiles of its successor before it ends).  The ticket after those is asked
+// for by thread 0 shortly before the current item ends, published through LDS ahead of a
+// barrier the item crosses anyway, and taken at the hand-over.  Asking late matters: a
+// workgroup that asks at the start of a long item reserves work it will not touch for a long
+// time, and in a step with about three items per workgroup that left half the chip idle while
+// the other half worked through its reservations.  The first two tickets of a workgroup are its
+// index plus 0 and 1 grids (the queue is in descending cost, so this deals the largest items
+// out evenly, and a workgroup starts without a round trip to the counter).
+constexpr int kDealtTickets = 2;
 struct Tickets {
   int cur, nxt;
-  int pending;   // meaningful in thread 0 only: the counter's reply, an offset from 3 grids
+  int pending;   // meaningful in thread 0 only: the counter's reply, an offset from the dealt tickets
   int parity;
 };
 
-// Hand-over to the next item: thread 0 publishes the ticket it holds through LDS (two slots
-// alternate, so one barrier per hand-over is enough) and asks for the one after it.
+// thread 0 asks the counter for one more ticket; the reply is first touched by tickets_publish
+__device__ __forceinline__ void tickets_reserve(Tickets& t, int* ctrl) {
+  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
+}
+// thread 0 puts the reserved ticket into LDS (two slots alternate, so one barrier per hand-over is enough)
 __device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
-  // the reply is first touched here, an item after it was asked for
-  if (threadIdx.x == 0) s_tk[t.parity] = 3 * (int)gridDim.x + t.pending;
+  if (threadIdx.x == 0) s_tk[t.parity] = kDealtTickets * (int)gridDim.x + t.pending;
 }
 // ... after a workgroup barrier that follows tickets_publish
-__device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk, int* ctrl) {
+__device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk) {
   t.cur = t.nxt;
   t.nxt = uniform(s_tk[t.parity]);
   t.parity ^= 1;
-  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
-}
-// The barrier also frees the LDS of the finished item.
-__device__ __forceinline__ void tickets_advance(Tickets& t, int* s_tk, int* ctrl) {
-  tickets_publish(t, s_tk);
-  __syncthreads();
-  tickets_take(t, s_tk, ctrl);
 }
 
 template <int D>
@@ -351,8 +351,13 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
     const int step = d.step, pe = d.pe, tend = d.tend, g = d.g;
     int pp = d.pp;
     int a0 = d.a0, a1 = d.a1, b0 = d.b0, b1 = d.b1;
+    bool reserved = false;
     // page ids are fetched one pair ahead of the KV loads that need them
     while (pp < pe) {
+      if (!reserved && pp + 4 * step >= pe) {   // a few pairs before the end (thread 0 sits in the first wavefront, which always has pairs)
+        tickets_reserve(t, ctrl);
+        reserved = true;
+      }
       if (pp + step < pe) decode_load<D>(r1, a.pool, b0, b1, Hkv, g, k_sel, k_off, v_sel, v_off);
       if (pp + 2 * step < pe) {
         a0 = decode_page(bt, d, pp + 2 * step);
@@ -377,6 +382,10 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
       }
       pp += step;
     }
+    // The reply to the ticket request has come back in front of the last pairs' loads (returns
+    // are in order), so publishing it here waits for nothing; after the requests below it would
+    // wait for them.  The barriers of the epilogue stand between this write and its readers.
+    tickets_publish(t, s_tk);
     // both register sets and the Q operand are free now: start on the next item
     if (carry_on) {
       if (dn.pp < dn.pe) decode_load<D>(r0, a.pool, dn.a0, dn.a1, Hkv, dn.g, k_sel, k_off, v_sel, v_off);
@@ -433,7 +442,8 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
         }
       }
     }
-    tickets_advance(t, s_tk, ctrl);   // its barrier also frees the LDS partials
+    __syncthreads();                  // frees the LDS partials; the ticket was published before the one above
+    tickets_take(t, s_tk);
     if (!carry_on) break;
     it = nx;
     d = dn;
@@ -682,7 +692,8 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, T
                                              const char* kcur, char* kfill, const __bf16* pool,
                                              const int* __restrict__ bt, const TileStream& ts, int kt, int wave_kend, int wave_pmin,
                                              int ctx_len, int Hkv, int k_lane, int v_lane, int j, float sl2,
-                                             int wave, int lane, bool publish, const Tickets& t, int* s_tk) {
+                                             int wave, int lane, bool publish, bool reserve, Tickets& t, int* s_tk,
+                                             int* ctrl) {
   const bool active = kt < wave_kend;
   const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
   const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
@@ -706,14 +717,14 @@ __device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, T
   if (kt + 32 < wave_kend) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
   else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
   if (publish) {
-    // First tile of an item: the ticket asked for at the last hand-over is published ahead of this
-    // tile's barrier, so that the hand-over at the end of the item needs no barrier of its own.
-    // It is done here, at the end of the tile, because reading the counter's reply makes the
-    // wavefront wait for everything it has in flight, and by now the result rows of the previous
-    // item have long reached memory.
+    // The ticket asked for a tile ago (or at the last hand-over) is published ahead of this tile's
+    // barrier, so that the hand-over at the end of the item needs no barrier of its own.  It is
+    // done at the end of the tile: reading the counter's reply makes the wavefront wait for
+    // whatever it had in flight when it asked.
     tickets_publish(t, s_tk);
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the LDS write has been performed
   }
+  if (reserve) tickets_reserve(t, ctrl);   // after the publish in program order: never both in one tile
   __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
   asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
 }
@@ -844,6 +855,18 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     ts.kb_n = nx.kb;
   };
   set_stream();
+  // Tiles (by first key) at whose end the next ticket is asked for and published: the last but
+  // two and the last but one of the item.  Items of one or two tiles ask at the hand-over and
+  // publish at the end of their first tile.
+  int publish_kt, reserve_kt;
+  auto set_ticket_points = [&]() {
+    const int n_tiles = (it.ke - it.kb + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
+    const int ip = n_tiles > 2 ? n_tiles - 2 : 0;
+    publish_kt = it.kb + ip * HFX_KEY_TILE;
+    reserve_kt = ip > 0 ? publish_kt - HFX_KEY_TILE : -1;
+    if (ip == 0) tickets_reserve(t, ctrl);
+  };
+  set_ticket_points();
 
   PrefillWave<D> w;
   WaveRows wr = wave_rows<D>(it, wave, n);
@@ -872,7 +895,8 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     int fill = cur + 2 * Smem<D>::kKBytes;
     if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
     prefill_tile<D>(w, tp, tn, gn, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
-                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane, kt == it.kb, t, s_tk);
+                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane, kt == publish_kt, kt == reserve_kt, t, s_tk,
+                    ctrl);
     cur += Smem<D>::kKBytes;
     if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
     kt += HFX_KEY_TILE;
@@ -881,11 +905,12 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     // hand-over: the item is finished; its successor's first tiles are already on their way
     const bool carry_on = ts.next_ok;
     prefill_store<D>(a, H, it, wr, w, Hq, wave, lane, stage);
-    tickets_take(t, s_tk, ctrl);
+    tickets_take(t, s_tk);
     if (!carry_on) break;
     it = nx;
     nx = items[t.nxt < n_items ? t.nxt : t.cur];
     set_stream();
+    set_ticket_points();
     wr = wave_rows<D>(it, wave, n);
     q_load<D>(w, a, it, wr, Hq, j);
     // Q is needed by the very next MFMA.  Waiting for it here, in so many words, also tells the
@@ -941,7 +966,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   Tickets t;
   t.cur = (int)blockIdx.x;
   t.nxt = (int)(blockIdx.x + gridDim.x);
-  t.pending = (int)blockIdx.x - (int)gridDim.x;
+  t.pending = 0;
   t.parity = 0;
   while (t.cur < n_items) {
     if (items[t.cur].type == HFX_ITEM_DECODE) {
