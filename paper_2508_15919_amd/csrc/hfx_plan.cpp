@@ -223,13 +223,18 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     std::vector<HfxItem>& sorted = P.sort_tmp;
     sorted.resize(n);
     if (dec_ns > pre_ns && pre_ns > 0.0) {
-      // A step whose decode work outweighs its prefill work: the two kinds alternate in blocks of half
-      // the planning width, decode first, each kind in descending cost.  With the first items dealt
-      // out by workgroup index, the lower half of the workgroups then starts on decode items and the
-      // upper half on prefill items, which puts one of each on every CU: the matrix work runs in
-      // the shadow of the memory-bound stream for as long as it lasts (measured on the Llama-8B-shaped
-      // mixed step: 5 % less time than plain descending order; on prefill-dominated steps the same
-      // interleave costs 2-13 %, so they keep the plain order).
+      // A step whose decode work outweighs its prefill work.  The first two items of workgroup b
+      // are queue positions b and b + HFX_PLAN_WGS, and workgroups b and b + HFX_PLAN_WGS/2 share a
+      // CU.  Over those two rounds the prefill items (largest first) go to the workgroups of the
+      // first `pair_cus` CUs, both workgroups of a CU, and the decode items to all the others:
+      // the matrix work then runs in the shadow of the memory-bound stream without sharing a
+      // CU's memory path with it (a prefill workgroup next to a decode workgroup on one CU saw its
+      // tiles take 2.5 times as long; measured on the Llama-8B-shaped mixed step, this layout takes
+      // 6 % less time than one workgroup of each kind per CU, which in turn took 5 % less than plain
+      // descending order).  pair_cus is sized so that the two rounds hold all prefill items, up to
+      // half the CUs.  Behind the two rounds the kinds alternate in blocks of half the planning
+      // width, decode first, each kind still in descending cost.  On prefill-dominated steps any
+      // such interleave costs 2-13 %, so they keep the plain order.
       constexpr size_t kBlockItems = HFX_PLAN_WGS / 2;
       std::vector<uint32_t>& dec = P.order_dec;
       std::vector<uint32_t>& pre = P.order_pre;
@@ -239,7 +244,14 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
         const uint32_t idx = (uint32_t)(a[i] & 0xffffffffu);
         (P.items[idx].type == HFX_ITEM_DECODE ? dec : pre).push_back(idx);
       }
+      const size_t pair_cus = std::min<size_t>((pre.size() + 3) / 4, kBlockItems / 2);
       size_t di = 0, pi = 0, o = 0;
+      for (int round = 0; round < 2; ++round)
+        for (size_t b = 0; b < (size_t)HFX_PLAN_WGS && o < n; ++b) {
+          const bool prefill_slot = (b % kBlockItems) < pair_cus;
+          if ((prefill_slot && pi < pre.size()) || di >= dec.size()) sorted[o++] = P.items[pre[pi++]];
+          else sorted[o++] = P.items[dec[di++]];
+        }
       while (di < dec.size() || pi < pre.size()) {
         for (size_t k = 0; k < kBlockItems && di < dec.size(); ++k) sorted[o++] = P.items[dec[di++]];
         for (size_t k = 0; k < kBlockItems && pi < pre.size(); ++k) sorted[o++] = P.items[pre[pi++]];

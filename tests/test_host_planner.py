@@ -65,10 +65,19 @@ def check_coverage(b, d):
     if len(pre_first) == 0 or len(pre_first) == len(items) or np.all(np.diff(items["cost"]) <= 0):
         pass                                   # one kind only, or plain descending order
     else:
-        # decode-dominated mixed step: blocks of 256, decode first, as long as both kinds last
+        # decode-dominated mixed step: over the first two rounds of 512 positions the prefill items sit
+        # at the positions of the workgroups of the first ceil(n_pre / 4) CUs (position mod 256), at
+        # most 128 of them; behind that, blocks of 256, decode first, as long as both kinds last
         ty = items["type"]
         n_dec, n_pre = int((ty == 0).sum()), int((ty == 1).sum())
+        pair_cus = min((n_pre + 3) // 4, 128)
         want = []
+        for pos in range(min(1024, n_dec + n_pre)):
+            slot = (pos % 512) % 256 < pair_cus
+            if (slot and n_pre) or not n_dec:
+                want.append(1); n_pre -= 1
+            else:
+                want.append(0); n_dec -= 1
         while n_dec or n_pre:
             k = min(256, n_dec); want += [0] * k; n_dec -= k
             k = min(256, n_pre); want += [1] * k; n_pre -= k
