@@ -181,13 +181,26 @@ def test_random_steps(hb, oracle, seed):
 
 def test_many_short_items_in_a_row(hb, oracle):
     """Far more items than resident workgroups, almost all of them one tile long: every workgroup chains
-    through dozens of hand-overs, first on its statically dealt items and then on counter tickets."""
+    through dozens of hand-overs, first on its two dealt items and then on counter tickets."""
     rng = np.random.default_rng(77)
     R = 700
     kinds = [PREFILL if i % 3 else DECODE for i in range(R)]
     ql = [int(rng.integers(1, 70)) if k == PREFILL else 1 for k in kinds]
     cl = [q if k == PREFILL else int(rng.integers(1, 200)) for k, q in zip(kinds, ql)]
     check_full(hb, oracle, synth.make_batch(32, 8, 128, kinds, ql, cl, 78, name="many-short"))
+
+
+def test_items_of_one_to_six_tiles_and_pairs(hb, oracle):
+    """The ticket for the item after next is asked for and published at tile (or page-pair) positions
+    that depend on how long the current item is: prompts whose row tiles see 1..6 key tiles and decodes
+    whose wavefronts walk 1..6 page pairs, far more of them than resident workgroups, in one queue."""
+    rng = np.random.default_rng(91)
+    kinds, ql, cl = [], [], []
+    for rep in range(40):
+        for tiles in range(1, 7):
+            kinds.append(PREFILL); ql.append(32); cl.append(64 * tiles - int(rng.integers(0, 31)))
+            kinds.append(DECODE); ql.append(1); cl.append(32 * tiles - int(rng.integers(0, 31)))
+    check_full(hb, oracle, synth.make_batch(32, 8, 128, kinds, ql, cl, 92, name="ticket-points"))
 
 
 def test_shared_prefix_pages(hb, oracle):
