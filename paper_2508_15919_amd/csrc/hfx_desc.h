@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 11u
+#define HFX_DESC_VERSION 12u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -63,11 +63,6 @@ struct HfxItem {
 // One merge group: nsplit partials of rows_per_split rows each, split s at workspace rows
 // base_row + s * rows_per_split.  type/req/h0/hn/row0 are those of the group's items and say
 // which output rows the merged result belongs to.
-// One workgroup of the merge launch: 8 / lanes rows of a group starting at row chunk * (8 / lanes),
-// where lanes (8 or 1) is how many threads share the splits of one row.
-struct HfxUnit {
-  int32_t group, chunk;
-};
 
 struct HfxGroup {
   int32_t nsplit;
@@ -75,4 +70,13 @@ struct HfxGroup {
   int32_t rows_per_split;
   int32_t type, req, h0, hn, row0;
   int32_t q_start, q_len;       /* of the request, so that the merge launch needs no third table */
+};
+
+// One workgroup of the merge launch: 8 / lanes rows of a group starting at row chunk * (8 / lanes),
+// where lanes (8 or 1) is how many threads share the splits of one row.  The record carries a copy
+// of its group, so that a merge workgroup reads one record and then the partials: every table
+// between the launch and the data is one more trip to memory in a launch that lasts microseconds.
+struct HfxUnit {
+  HfxGroup g;
+  int32_t group, chunk;
 };

@@ -78,43 +78,41 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 // (one row per workgroup) so that all loads are in flight together, for groups with at most 8
 // splits one thread takes them all (8 rows per workgroup).
 // ----------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __restrict__ units,
-                                                               const HfxGroup* __restrict__ groups,
-                                                               const float* __restrict__ ws,
-                                                               const float* __restrict__ ml, int Hq, int G,
-                                                               __bf16* __restrict__ out) {
+// The body of the merge for a group whose threads see at most N splits each.
+template <int D, int N>
+__device__ __forceinline__ void merge_rows(const HfxUnit& un, const float* __restrict__ ws, const float* __restrict__ ml,
+                                           int Hq, int G, __bf16* __restrict__ out, float* s_max, float* s_l,
+                                           f32x4 (*s_acc)[D / 4]) {
   constexpr int C4 = D / 4;                       // float4 columns of a row
-  constexpr int Q = HFX_WG_THREADS / C4;          // threads per column: 8 (D = 128) or 16 (D = 64)
-  __shared__ float s_max[Q];
-  __shared__ float s_l[Q];
-  __shared__ f32x4 s_acc[Q][C4];
-  // everything the launch can know on the host comes in as an argument: unit -> group -> partials
-  // is the whole chain of dependent loads
-  const HfxUnit un = units[blockIdx.x];
-  const HfxGroup gr = groups[un.group];
+  const HfxGroup& gr = un.g;
   const int tid = threadIdx.x;
   const int col = tid % C4, q = tid / C4;
-  const bool wide = gr.nsplit > 8;                // Q... only the first 8 thread rows are used below
+  const bool wide = N == 8 && gr.nsplit > 8;      // only the first 8 thread rows are used below
   const int SL = wide ? 8 : 1;                    // threads sharing one row's splits
   const int sl = wide ? q : 0;
   const int row = wide ? un.chunk : un.chunk * 8 + q;
   const bool row_ok = q < 8 && row < gr.rows_per_split;
   const int rows = gr.rows_per_split, ns = gr.nsplit, base = gr.base_row;
-  float mv[8], lv[8];
+  // All loads are issued without lane predicates (a thread without a split in a slot, or outside
+  // the group's rows, reads a neighbour's partial and gives it weight 0): under per-lane
+  // conditions the compiler waits for each slot's loads before it asks for the next.
+  const int row_c = row < rows ? row : rows - 1;
+  float mv[N], lv[N];
+  f32x4 av[N];
+  bool ok[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {                   // the planner never makes more than 64 splits
+    const int s = sl + i * SL;
+    ok[i] = row_ok && s < ns;
+    const long pr = (long)base + (long)(s < ns ? s : ns - 1) * rows + row_c;
+    const float2 t = *reinterpret_cast<const float2*>(ml + pr * 2);
+    mv[i] = t.x;
+    lv[i] = t.y;
+    av[i] = *reinterpret_cast<const f32x4*>(ws + pr * D + col * 4);
+  }
   float mloc = NEG_INF;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {                   // the planner never makes more than 64 splits
-    const int s = sl + i * SL;
-    mv[i] = NEG_INF;
-    lv[i] = 0.f;
-    if (row_ok && s < ns) {
-      const long pr = (long)base + (long)s * rows + row;
-      mv[i] = ml[pr * 2];
-      lv[i] = ml[pr * 2 + 1];
-    }
-    mloc = fmaxf(mloc, mv[i]);
-  }
+  for (int i = 0; i < N; ++i) mloc = fmaxf(mloc, ok[i] ? mv[i] : NEG_INF);
   float mm = mloc;
   if (wide) {
     if (col == 0) s_max[q] = mloc;
@@ -125,14 +123,10 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __
   float ll = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int s = sl + i * SL;
-    if (row_ok && s < ns) {
-      const long pr = (long)base + (long)s * rows + row;
-      const float w = fast_exp2(mv[i] - mm);
-      ll += lv[i] * w;
-      o += *reinterpret_cast<const f32x4*>(ws + pr * D + col * 4) * w;
-    }
+  for (int i = 0; i < N; ++i) {
+    const float w = ok[i] ? fast_exp2(mv[i] - mm) : 0.f;
+    ll += lv[i] * w;
+    o += av[i] * w;
   }
   if (wide) {
     s_acc[q][col] = o;
@@ -161,6 +155,26 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __
 #pragma unroll
   for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(o[e] * inv);
   *reinterpret_cast<bf16x4*>(out + orow * D + col * 4) = ob;
+}
+
+template <int D>
+__global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __restrict__ units,
+                                                               const float* __restrict__ ws,
+                                                               const float* __restrict__ ml, int Hq, int G,
+                                                               __bf16* __restrict__ out) {
+  constexpr int Q = HFX_WG_THREADS / (D / 4);     // threads per column: 8 (D = 128) or 16 (D = 64)
+  __shared__ float s_max[Q];
+  __shared__ float s_l[Q];
+  __shared__ f32x4 s_acc[Q][D / 4];
+  // Everything the launch can know on the host comes in as an argument, and the unit record holds a
+  // copy of its group: unit -> partials is the whole chain of dependent loads, and the (m, l) pairs
+  // and the accumulator rows of all splits are asked for together.  One copy of the body per
+  // number of slots, so that a group of two splits does not pay for eight.
+  const HfxUnit un = units[blockIdx.x];
+  const int ns = un.g.nsplit;
+  if (ns <= 2) merge_rows<D, 2>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
+  else if (ns <= 4) merge_rows<D, 4>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
+  else merge_rows<D, 8>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1097,13 +1111,12 @@ hipError_t launch_mixed_attention(const HfxHeader& h, int grid, void* desc, cons
     hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, h, d, ctrl, qp, pp, wp, op);
   if (n_units > 0) {
     const HfxUnit* units = reinterpret_cast<const HfxUnit*>(d + h.off_units);
-    const HfxGroup* groups = reinterpret_cast<const HfxGroup*>(d + h.off_groups);
     const float* ml = reinterpret_cast<const float*>(static_cast<const char*>(ws) + h.ws_off_ml);
     const int Hq = h.num_q_heads, G = h.num_q_heads / h.num_kv_heads;
     if (head_dim == 128)
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, wp, ml, Hq, G, op);
     else
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, wp, ml, Hq, G, op);
   }
   return hipGetLastError();
 }
