@@ -316,9 +316,7 @@ def parse_desc(host_desc: np.ndarray) -> dict:
         "bt": buf[h.off_bt:h.off_bt + 4 * h.n_bt].view(np.int32),
         "items": buf[h.off_items:h.off_items + ITEM_DTYPE.itemsize * h.n_items].view(ITEM_DTYPE),
         "groups": buf[h.off_groups:h.off_groups + GROUP_DTYPE.itemsize * h.n_groups].view(GROUP_DTYPE),
-        # a unit record is a copy of its group (10 words) followed by (group, chunk)
-        "units": buf[h.off_units:h.off_units + 48 * h.n_units].view(np.int32).reshape(-1, 12)[:, 10:12],
-        "unit_groups": buf[h.off_units:h.off_units + 48 * h.n_units].view(np.int32).reshape(-1, 12)[:, :10],
+        "units": buf[h.off_units:h.off_units + 8 * h.n_units].view(np.int32).reshape(-1, 2),
     }
 
 

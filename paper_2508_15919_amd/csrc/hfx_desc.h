@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 12u
+#define HFX_DESC_VERSION 13u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -73,10 +73,7 @@ struct HfxGroup {
 };
 
 // One workgroup of the merge launch: 8 / lanes rows of a group starting at row chunk * (8 / lanes),
-// where lanes (8 or 1) is how many threads share the splits of one row.  The record carries a copy
-// of its group, so that a merge workgroup reads one record and then the partials: every table
-// between the launch and the data is one more trip to memory in a launch that lasts microseconds.
+// where lanes (8 or 1) is how many threads share the splits of one row.
 struct HfxUnit {
-  HfxGroup g;
   int32_t group, chunk;
 };

@@ -80,11 +80,10 @@ __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
 // ----------------------------------------------------------------------------------------------
 // The body of the merge for a group whose threads see at most N splits each.
 template <int D, int N>
-__device__ __forceinline__ void merge_rows(const HfxUnit& un, const float* __restrict__ ws, const float* __restrict__ ml,
+__device__ __forceinline__ void merge_rows(const HfxUnit& un, const HfxGroup& gr, const float* __restrict__ ws, const float* __restrict__ ml,
                                            int Hq, int G, __bf16* __restrict__ out, float* s_max, float* s_l,
                                            f32x4 (*s_acc)[D / 4]) {
   constexpr int C4 = D / 4;                       // float4 columns of a row
-  const HfxGroup& gr = un.g;
   const int tid = threadIdx.x;
   const int col = tid % C4, q = tid / C4;
   const bool wide = N == 8 && gr.nsplit > 8;      // only the first 8 thread rows are used below
@@ -159,6 +158,7 @@ __device__ __forceinline__ void merge_rows(const HfxUnit& un, const float* __res
 
 template <int D>
 __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __restrict__ units,
+                                                               const HfxGroup* __restrict__ groups,
                                                                const float* __restrict__ ws,
                                                                const float* __restrict__ ml, int Hq, int G,
                                                                __bf16* __restrict__ out) {
@@ -166,15 +166,17 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __
   __shared__ float s_max[Q];
   __shared__ float s_l[Q];
   __shared__ f32x4 s_acc[Q][D / 4];
-  // Everything the launch can know on the host comes in as an argument, and the unit record holds a
-  // copy of its group: unit -> partials is the whole chain of dependent loads, and the (m, l) pairs
-  // and the accumulator rows of all splits are asked for together.  One copy of the body per
-  // number of slots, so that a group of two splits does not pay for eight.
+  // Everything the launch can know on the host comes in as an argument: unit -> group -> partials
+  // is the whole chain of dependent loads, and the (m, l) pairs and the accumulator rows of all
+  // splits are asked for together.  One copy of the body per number of slots, so that a group of
+  // two splits does not pay for eight.  (A unit record that carried a copy of its group saved one
+  // trip, about a microsecond, and cost the host ten to write and upload.)
   const HfxUnit un = units[blockIdx.x];
-  const int ns = un.g.nsplit;
-  if (ns <= 2) merge_rows<D, 2>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
-  else if (ns <= 4) merge_rows<D, 4>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
-  else merge_rows<D, 8>(un, ws, ml, Hq, G, out, s_max, s_l, s_acc);
+  const HfxGroup gr = groups[un.group];
+  const int ns = gr.nsplit;
+  if (ns <= 2) merge_rows<D, 2>(un, gr, ws, ml, Hq, G, out, s_max, s_l, s_acc);
+  else if (ns <= 4) merge_rows<D, 4>(un, gr, ws, ml, Hq, G, out, s_max, s_l, s_acc);
+  else merge_rows<D, 8>(un, gr, ws, ml, Hq, G, out, s_max, s_l, s_acc);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1111,12 +1113,13 @@ hipError_t launch_mixed_attention(const HfxHeader& h, int grid, void* desc, cons
     hipLaunchKernelGGL(mixed_attention_kernel<64>, dim3(grid), dim3(HFX_WG_THREADS), 0, stream, h, d, ctrl, qp, pp, wp, op);
   if (n_units > 0) {
     const HfxUnit* units = reinterpret_cast<const HfxUnit*>(d + h.off_units);
+    const HfxGroup* groups = reinterpret_cast<const HfxGroup*>(d + h.off_groups);
     const float* ml = reinterpret_cast<const float*>(static_cast<const char*>(ws) + h.ws_off_ml);
     const int Hq = h.num_q_heads, G = h.num_q_heads / h.num_kv_heads;
     if (head_dim == 128)
-      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, wp, ml, Hq, G, op);
+      hipLaunchKernelGGL(merge_kernel<128>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
     else
-      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, wp, ml, Hq, G, op);
+      hipLaunchKernelGGL(merge_kernel<64>, dim3(n_units), dim3(HFX_WG_THREADS), 0, stream, units, groups, wp, ml, Hq, G, op);
   }
   return hipGetLastError();
 }

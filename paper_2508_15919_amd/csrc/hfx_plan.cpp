@@ -267,7 +267,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   for (size_t gi = 0; gi < P.groups.size(); ++gi) {
     const int rows_per_unit = P.groups[gi].nsplit > 8 ? 1 : 8;
     for (int c = 0; c * rows_per_unit < P.groups[gi].rows_per_split; ++c) {
-      HfxUnit u = {P.groups[gi], (int32_t)gi, c};
+      HfxUnit u = {(int32_t)gi, c};
       P.units.push_back(u);
     }
   }
