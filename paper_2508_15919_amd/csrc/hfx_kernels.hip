@@ -206,9 +206,14 @@ struct Tickets {
   int parity;
 };
 
-// thread 0 asks the counter for one more ticket; the reply is first touched by tickets_publish
-__device__ __forceinline__ void tickets_reserve(Tickets& t, int* ctrl) {
-  if (threadIdx.x == 0) t.pending = atomicAdd(ctrl, 1);
+// Thread 0 asks the counter for one more ticket (when `ask`); the reply is first touched by
+// tickets_publish.  The other lanes, and a call with ask == false, set the field to zero rather
+// than keep what it held: keeping it reads the register the previous request wrote, and for that
+// the compiler puts a wait for everything in flight in front of this request.
+__device__ __forceinline__ void tickets_reserve(Tickets& t, int* ctrl, bool ask = true) {
+  int r = 0;
+  if (ask && threadIdx.x == 0) r = atomicAdd(ctrl, 1);
+  t.pending = r;
 }
 // thread 0 puts the reserved ticket into LDS (two slots alternate, so one barrier per hand-over is enough)
 __device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
@@ -880,7 +885,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     const int ip = n_tiles > 2 ? n_tiles - 2 : 0;
     publish_kt = it.kb + ip * HFX_KEY_TILE;
     reserve_kt = ip > 0 ? publish_kt - HFX_KEY_TILE : -1;
-    if (ip == 0) tickets_reserve(t, ctrl);
+    tickets_reserve(t, ctrl, ip == 0);   // the field is dead here: the last publish has read it
   };
   set_ticket_points();
 
@@ -924,8 +929,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     tickets_take(t, s_tk);
     if (!carry_on) break;
     it = nx;
-    nx = items[t.nxt < n_items ? t.nxt : t.cur];
-    set_stream();
+    nx = items[t.nxt < n_items ? t.nxt : t.cur];   // asked for here, first looked at behind the wait for Q
     set_ticket_points();
     wr = wave_rows<D>(it, wave, n);
     q_load<D>(w, a, it, wr, Hq, j);
@@ -933,6 +937,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     // compiler that nothing is in flight when the tile loop is re-entered; left to itself it
     // carries the Q loads into the loop as pending and drains the queue down to them on every tile.
     HFX_WAIT_VMCNT(0);
+    set_stream();
 #pragma unroll
     for (int b = 0; b < D / 32; ++b)
 #pragma unroll
