@@ -912,7 +912,19 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   int cur = 0;   // byte offset of the K buffer holding the current tile; the one two ahead is refilled
+  bool recopy = false;
   for (;;) {
+    if (recopy) {
+      // first tile of a one-tile item: the stream position after it belongs to an item that was
+      // not known yet when that position's copy was issued; request it again, now with the right
+      // pages.  (Issued here rather than at the hand-over: there the compiler closes the block
+      // with a wait for everything in flight, which would include this copy.)
+      int nb = cur + Smem<D>::kKBytes;
+      if (nb >= 3 * Smem<D>::kKBytes) nb = 0;
+      tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
+      k_tile_async<D>(smem + nb, a.pool, tn, Hkv, gn, wave, lane);
+      recopy = false;
+    }
     int fill = cur + 2 * Smem<D>::kKBytes;
     if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
     prefill_tile<D>(w, tp, tn, gn, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
@@ -945,14 +957,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     w.m = NEG_INF;
     w.l = 0.f;
     kt = it.kb;
-    if (kt + HFX_KEY_TILE >= it.ke) {
-      // a one-tile item: the stream position after it belongs to an item that was not known yet
-      // when that position's copy was issued; request it again, now with the right pages
-      int nb = cur + Smem<D>::kKBytes;
-      if (nb >= 3 * Smem<D>::kKBytes) nb = 0;
-      tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
-      k_tile_async<D>(smem + nb, a.pool, tn, Hkv, gn, wave, lane);
-    }
+    recopy = kt + HFX_KEY_TILE >= it.ke;
   }
   HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the stream
   __syncthreads();     // ... by every wavefront, before the LDS is used for anything else
