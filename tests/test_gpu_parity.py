@@ -203,6 +203,22 @@ def test_items_of_one_to_six_tiles_and_pairs(hb, oracle):
     check_full(hb, oracle, synth.make_batch(32, 8, 128, kinds, ql, cl, 92, name="ticket-points"))
 
 
+def test_merge_of_two_to_sixty_splits(hb, oracle):
+    """The merge launch has one body per slot count (2, 4, 8) and a wide form above 8 splits: decode
+    contexts cut into 2, 3, 4, 5, 8, 9, 16, about 40 and about 60 pieces, and a prompt chunk on a
+    long prior context whose row tiles are split along the keys."""
+    ctx = [300, 500, 700, 900, 1450, 1650, 2950, 7400, 13000]
+    kinds = [DECODE] * len(ctx) + [PREFILL]
+    ql = [1] * len(ctx) + [96]
+    cl = ctx + [6000]
+    b = synth.make_batch(32, 8, 128, kinds, ql, cl, 93, name="split-counts")
+    d = hb.parse_desc(hb.DeviceStep(b).host_desc.numpy())
+    nsplit = sorted(set(int(x) for x in d["groups"]["nsplit"]))
+    assert nsplit[0] == 2 and nsplit[-1] > 48 and any(2 < x <= 4 for x in nsplit) and any(4 < x <= 8 for x in nsplit) \
+        and any(8 < x <= 16 for x in nsplit), nsplit
+    check_full(hb, oracle, b)
+
+
 def test_shared_prefix_pages(hb, oracle):
     b = synth.make_batch(32, 8, 128, [DECODE, DECODE, PREFILL], [1, 1, 40], [300, 300, 296], 13)
     n = 16
