@@ -95,9 +95,14 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   P.total_q = (int32_t)T;
   P.n_bt = (int32_t)nbt;
   const double total_ns = dec_ns + pre_ns;
-  // decode pieces are sized against the decode work alone: in a step dominated by prefill they stay
-  // small and fill the gaps between the large prefill items
-  const double cap_ns = std::max(dec_ns / (HFX_PLAN_WGS * kDecodeItemsPerWg), kMinItemNs);
+  // Decode pieces are sized against the decode work alone (in a step dominated by prefill they stay
+  // small and fill the gaps between the large prefill items), for a whole number of rounds of the
+  // planning width: as many rounds as fit pieces of at least the minimum size, at most
+  // kDecodeItemsPerWg.  A step with work for 2.4 rounds of minimum-size pieces is better served by
+  // two rounds of larger ones than by a third, half-empty round.
+  double rounds = std::floor(dec_ns / (HFX_PLAN_WGS * kMinItemNs));
+  rounds = std::min<double>(std::max(rounds, 1.0), kDecodeItemsPerWg);
+  const double cap_ns = std::max(dec_ns / (HFX_PLAN_WGS * rounds), kMinItemNs);
   const double cap_prefill_ns = std::max(total_ns / (HFX_PLAN_WGS * kPrefillItemsPerWg), kMinItemNs);
 
   int64_t rows = 0;
