@@ -293,7 +293,8 @@ class DescHeader(ctypes.Structure):
                 ("off_items", ctypes.c_uint32), ("off_groups", ctypes.c_uint32), ("n_ctrl", ctypes.c_uint32),
                 ("total_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
                 ("ws_off_ml", ctypes.c_uint64), ("max_group_rows", ctypes.c_int32),
-                ("n_units", ctypes.c_int32), ("off_units", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 5)]
+                ("n_units", ctypes.c_int32), ("off_units", ctypes.c_uint32), ("n_runs", ctypes.c_int32),
+                ("off_runs", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 3)]
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
@@ -317,6 +318,8 @@ def parse_desc(host_desc: np.ndarray) -> dict:
         "items": buf[h.off_items:h.off_items + ITEM_DTYPE.itemsize * h.n_items].view(ITEM_DTYPE),
         "groups": buf[h.off_groups:h.off_groups + GROUP_DTYPE.itemsize * h.n_groups].view(GROUP_DTYPE),
         "units": buf[h.off_units:h.off_units + 8 * h.n_units].view(np.int32).reshape(-1, 2),
+        # append runs: (first packed row, tokens, physical page, first slot)
+        "runs": buf[h.off_runs:h.off_runs + 16 * h.n_runs].view(np.int32).reshape(-1, 4),
     }
 
 

@@ -168,9 +168,7 @@ hfx_status hfx_append_kv(const hfx_shape* shape, const void* k_new, const void* 
   hfx_status st = check_header(shape, host_desc, &h);
   if (st != HFX_OK) return st;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(kv_pool) || !aligned16(device_desc)) return HFX_ERR_ALIGN;
-  const long pieces = (long)h.total_q * h.num_kv_heads * (h.head_dim / 8);
-  if (hfx::launch_append_kv(device_desc, k_new, v_new, kv_pool, pieces, static_cast<hipStream_t>(stream)) !=
-      hipSuccess)
+  if (hfx::launch_append_kv(h, device_desc, k_new, v_new, kv_pool, static_cast<hipStream_t>(stream)) != hipSuccess)
     return HFX_ERR_DEVICE;
   return HFX_OK;
 }

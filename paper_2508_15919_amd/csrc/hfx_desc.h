@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 13u
+#define HFX_DESC_VERSION 14u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -30,7 +30,9 @@ struct HfxHeader {
   int32_t max_group_rows;       /* largest rows_per_split over the groups */
   int32_t n_units;              /* merge work units (one workgroup each) */
   uint32_t off_units;
-  uint32_t reserved[5];
+  int32_t n_runs;               /* append runs: the new tokens of the step, cut at page boundaries */
+  uint32_t off_runs;
+  uint32_t reserved[3];
 };
 
 struct HfxReq {
@@ -42,6 +44,12 @@ struct HfxReq {
                                    n_pages repeat the last page, so that a tile's four ids can be fetched
                                    as one aligned quad without clamping, a little way past the end */
   int32_t pad1;
+};
+
+// The new tokens of one request that fall into one page: packed query rows [row0, row0 + n) go to
+// slots [slot0, slot0 + n) of physical page `page`.  What the KV append walks.
+struct HfxRun {
+  int32_t row0, n, page, slot0;
 };
 
 // One unit of work for one workgroup.

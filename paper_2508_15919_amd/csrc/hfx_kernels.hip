@@ -1065,39 +1065,75 @@ __global__ void gather_kv_kernel(const char* desc, const uint16_t* pool, int req
   }
 }
 
-// KV append: one thread per 16-byte piece (8 dimensions) of one new token's K or V for one kv-head.
-// K pieces land as 16 contiguous bytes of the page's K block (blocked by 16 dimensions); V pieces
-// scatter as eight 2-byte stores down a column of the dimension-major V block.
-__global__ void append_kv_kernel(const char* __restrict__ desc, const uint16_t* __restrict__ k_new,
-                                 const uint16_t* __restrict__ v_new, uint16_t* __restrict__ pool) {
-  const HfxHeader* H = reinterpret_cast<const HfxHeader*>(desc);
-  const HfxReq* reqs = reinterpret_cast<const HfxReq*>(desc + H->off_req);
-  const int* bt_all = reinterpret_cast<const int*>(desc + H->off_bt);
-  const int Hkv = H->num_kv_heads, D = H->head_dim, R = H->num_requests;
-  const int pieces = D / 8;
-  const long total = (long)H->total_q * Hkv * pieces;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-    const int pc = (int)(i % pieces);
-    const int g = (int)((i / pieces) % Hkv);
-    const int row = (int)(i / ((long)pieces * Hkv));
-    // request owning packed row `row`: binary search over q_start
-    int lo = 0, hi = R - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (reqs[mid].q_start <= row) lo = mid; else hi = mid - 1;
-    }
-    const HfxReq rq = reqs[lo];
-    const int t = rq.ctx_len - rq.q_len + (row - rq.q_start);
-    const long pg = bt_all[rq.bt_start + t / HFX_PAGE];
-    const int slot = t % HFX_PAGE;
-    const long blk = ((pg * Hkv + g) * 2) * (16L * D);
-    const long src = ((long)row * Hkv + g) * D + pc * 8;
-    const int d0 = pc * 8;
-    u32x4 kv = *reinterpret_cast<const u32x4*>(k_new + src);
-    *reinterpret_cast<u32x4*>(pool + blk + ((long)(d0 / 16) * HFX_PAGE + slot) * 16 + d0 % 16) = kv;
-    uint16_t* vdst = pool + blk + 16L * D + (long)d0 * HFX_PAGE + slot;
+// KV append: one workgroup per (run, kv-head), a run being the new tokens of one request that fall
+// into one page (at most 16 consecutive slots).  The tokens' K and V rows for the head are read in
+// whole rows into LDS and leave in the pool's block order: a K piece of 16 dimensions is 32
+// contiguous bytes per slot, and a V row (one dimension) gets its run of slots as one contiguous
+// piece -- stored token by token, the dimension-major V block took one 2-byte request per
+// (token, dimension), which was most of the launch.  D threads; rows are padded by one word in LDS
+// so that a column walk does not stay on one bank.
+template <int D>
+__global__ __launch_bounds__(D) void append_kv_kernel(const HfxRun* __restrict__ runs, int Hkv,
+                                                      const uint16_t* __restrict__ k_new,
+                                                      const uint16_t* __restrict__ v_new,
+                                                      uint16_t* __restrict__ pool) {
+  constexpr int LD = D + 2;                       // LDS row stride in elements
+  __shared__ uint16_t sk[HFX_PAGE * LD];
+  __shared__ uint16_t sv[HFX_PAGE * LD];
+  const HfxRun run = runs[blockIdx.x];
+  const int g = blockIdx.y;
+  const int tid = threadIdx.x;
+  // rows in: thread t takes 2 elements of each token's row (4-byte loads, a row is D*2 bytes contiguous)
+  for (int i = tid; i < run.n * (D / 2); i += D) {
+    const int tok = i / (D / 2), e2 = i % (D / 2);
+    const long src = ((long)(run.row0 + tok) * Hkv + g) * D + e2 * 2;
+    *reinterpret_cast<uint32_t*>(&sk[tok * LD + e2 * 2]) = *reinterpret_cast<const uint32_t*>(k_new + src);
+    *reinterpret_cast<uint32_t*>(&sv[tok * LD + e2 * 2]) = *reinterpret_cast<const uint32_t*>(v_new + src);
+  }
+  __syncthreads();
+  uint16_t* kblk = pool + (((long)run.page * Hkv + g) * 2) * (16L * D);
+  uint16_t* vblk = kblk + 16L * D;
+  // K block [D/16][16 slots][16]: 2 D pieces of 16 bytes, piece u = (dimension group u / 32, slot
+  // (u % 32) / 2, half u % 2); consecutive threads write consecutive pieces
 #pragma unroll
-    for (int e = 0; e < 8; ++e) vdst[e * HFX_PAGE] = v_new[src + e];
+  for (int u = tid; u < 2 * D; u += D) {
+    const int slot = (u % 32) / 2;
+    if (slot >= run.slot0 && slot < run.slot0 + run.n) {
+      const uint16_t* src = &sk[(slot - run.slot0) * LD + (u / 32) * 16 + (u % 2) * 8];
+      u32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = *reinterpret_cast<const uint32_t*>(src + 2 * e);
+      *reinterpret_cast<u32x4*>(kblk + u * 8) = v;
+    }
+  }
+  // V block [D][16 slots]: a row (one dimension) is 32 bytes
+  if (run.slot0 == 0 && run.n == HFX_PAGE) {
+    // a whole page: 2 D pieces of 16 bytes, piece u = (dimension u / 2, slots 8 (u % 2) ..)
+#pragma unroll
+    for (int u = tid; u < 2 * D; u += D) {
+      const int d = u >> 1, s0 = (u & 1) * 8;
+      u32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v[e] = (uint32_t)sv[(s0 + 2 * e) * LD + d] | ((uint32_t)sv[(s0 + 2 * e + 1) * LD + d] << 16);
+      *reinterpret_cast<u32x4*>(vblk + u * 8) = v;
+    }
+  } else {
+    // part of a page: thread d writes its row's slots, two at a time where both belong to the run
+    const int d = tid;
+    uint16_t* dst = vblk + (long)d * HFX_PAGE;
+    const int lo = run.slot0, hi = run.slot0 + run.n;
+#pragma unroll
+    for (int w = 0; w < HFX_PAGE / 2; ++w) {
+      const int a = 2 * w, b = 2 * w + 1;
+      const bool in_a = a >= lo && a < hi, in_b = b >= lo && b < hi;
+      if (in_a && in_b)
+        *reinterpret_cast<uint32_t*>(dst + a) = (uint32_t)sv[(a - lo) * LD + d] | ((uint32_t)sv[(b - lo) * LD + d] << 16);
+      else if (in_a)
+        dst[a] = sv[(a - lo) * LD + d];
+      else if (in_b)
+        dst[b] = sv[(b - lo) * LD + d];
+    }
   }
 }
 
@@ -1157,14 +1193,19 @@ hipError_t launch_gather_kv(const void* desc, const void* pool, int request, lon
   return hipGetLastError();
 }
 
-hipError_t launch_append_kv(const void* desc, const void* k_new, const void* v_new, void* pool, long pieces,
+hipError_t launch_append_kv(const HfxHeader& h, const void* desc, const void* k_new, const void* v_new, void* pool,
                             hipStream_t stream) {
-  long blocks = (pieces + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                     static_cast<const char*>(desc), static_cast<const uint16_t*>(k_new),
-                     static_cast<const uint16_t*>(v_new), static_cast<uint16_t*>(pool));
+  if (h.n_runs <= 0) return hipSuccess;
+  const HfxRun* runs = reinterpret_cast<const HfxRun*>(static_cast<const char*>(desc) + h.off_runs);
+  const dim3 grid((unsigned)h.n_runs, (unsigned)h.num_kv_heads);
+  if (h.head_dim == 128)
+    hipLaunchKernelGGL(append_kv_kernel<128>, grid, dim3(128), 0, stream, runs, h.num_kv_heads,
+                       static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                       static_cast<uint16_t*>(pool));
+  else
+    hipLaunchKernelGGL(append_kv_kernel<64>, grid, dim3(64), 0, stream, runs, h.num_kv_heads,
+                       static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                       static_cast<uint16_t*>(pool));
   return hipGetLastError();
 }
 

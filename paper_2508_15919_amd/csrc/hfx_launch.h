@@ -12,7 +12,7 @@ hipError_t launch_mixed_attention(const HfxHeader& header, int grid, void* desc,
 hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
                             void* v_out, hipStream_t stream);
 
-hipError_t launch_append_kv(const void* desc, const void* k_new, const void* v_new, void* pool, long pieces,
+hipError_t launch_append_kv(const HfxHeader& h, const void* desc, const void* k_new, const void* v_new, void* pool,
                             hipStream_t stream);
 
 hipError_t launch_copy_pages(const void* pairs, long n_pairs, int units_per_page, const void* src, void* dst,

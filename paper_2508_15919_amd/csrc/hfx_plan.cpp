@@ -94,6 +94,10 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   }
   P.total_q = (int32_t)T;
   P.n_bt = (int32_t)nbt;
+  int64_t n_runs = 0;   // pages touched by each request's new tokens
+  for (int r = 0; r < R; ++r)
+    n_runs += (ctx_len[r] - 1) / HFX_PAGE - (ctx_len[r] - q_len[r]) / HFX_PAGE + 1;
+  P.n_runs = (int32_t)n_runs;
   const double total_ns = dec_ns + pre_ns;
   // Decode pieces are sized against the decode work alone (in a step dominated by prefill they stay
   // small and fill the gaps between the large prefill items), for a whole number of rounds of the
@@ -317,7 +321,10 @@ void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
   off = align_up(off + sizeof(HfxGroup) * P.groups.size(), 64);
   h->off_units = (uint32_t)off;
   h->n_units = (int32_t)P.units.size();
-  off = align_up(off + sizeof(HfxUnit) * P.units.size(), 256);
+  off = align_up(off + sizeof(HfxUnit) * P.units.size(), 64);
+  h->off_runs = (uint32_t)off;
+  h->n_runs = P.n_runs;
+  off = align_up(off + sizeof(HfxRun) * (uint64_t)P.n_runs, 256);
   h->total_bytes = off;
   uint64_t acc_bytes = align_up((uint64_t)P.n_partial_rows * shape->head_dim * 4ull, 256);
   h->ws_off_ml = acc_bytes;
@@ -361,7 +368,21 @@ hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, 
   put(h.off_bt + 4ull * (uint64_t)P.n_bt, nullptr, 0, h.off_items);
   put(h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size(), h.off_groups);
   put(h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size(), h.off_units);
-  put(h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size(), h.total_bytes);
+  put(h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size(), h.off_runs);
+  // append runs: each request's new tokens, cut at page boundaries
+  HfxRun* run = (HfxRun*)(base + h.off_runs);
+  for (int r = 0; r < R; ++r) {
+    const HfxReq& q = P.reqs[(size_t)r];
+    const int32_t* pages = bt_pages + bt_indptr[r];
+    int32_t t = q.ctx_len - q.q_len;
+    while (t < q.ctx_len) {
+      const int32_t slot0 = t % HFX_PAGE;
+      const int32_t n = std::min<int32_t>(HFX_PAGE - slot0, q.ctx_len - t);
+      *run++ = HfxRun{q.q_start + (t - (q.ctx_len - q.q_len)), n, pages[t / HFX_PAGE], slot0};
+      t += n;
+    }
+  }
+  put(h.off_runs + sizeof(HfxRun) * (uint64_t)P.n_runs, nullptr, 0, h.total_bytes);
   return HFX_OK;
 }
 

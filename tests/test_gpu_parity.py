@@ -259,6 +259,30 @@ def test_append_kv_is_bit_exact_and_feeds_attention(hb, oracle, idx, scale):
     err = np.abs(got - oracle.attention_batch(b))
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
 
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 1, 64), (8, 2, 128)])
+def test_append_kv_runs_that_start_and_end_inside_pages(hb, oracle, Hq, Hkv, D):
+    """The append walks the new tokens page by page: chunks whose first and last tokens fall anywhere in a
+    page (runs of 1 to 16 slots at every offset), next to single decode tokens at every slot."""
+    import torch
+    rng = np.random.default_rng(7 * Hq + D)
+    kinds, ql, cl = [], [], []
+    for slot in range(16):
+        kinds.append(DECODE); ql.append(1); cl.append(40 + slot)
+    for _ in range(40):
+        q = int(rng.integers(1, 70)); prior = int(rng.integers(0, 100))
+        kinds.append(PREFILL); ql.append(q); cl.append(prior + q)
+    b = synth.make_batch(Hq, Hkv, D, kinds, ql, cl, 95, name="append-runs")
+    T = b.total_q
+    k_new = synth.f32_to_bf16_bits(rng.standard_normal((T, Hkv, D)).astype(np.float32))
+    v_new = synth.f32_to_bf16_bits(rng.standard_normal((T, Hkv, D)).astype(np.float32))
+    step = hb.DeviceStep(b)
+    hb.hfx_append_kv(step.shape, torch.from_numpy(k_new.view(np.int16)).cuda(), torch.from_numpy(v_new.view(np.int16)).cuda(),
+                     step.pool, step.host_desc, step.device_desc, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    oracle.append_kv(Hkv, D, b.num_pages, b.q_len, b.ctx_len, b.bt_indptr, b.bt_pages, k_new, v_new, b.pool)
+    assert np.array_equal(step.pool.cpu().numpy().view(np.uint16), b.pool), "pool after append must match bit for bit"
+
+
 @pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 1, 64), (12, 12, 128)])
 def test_copy_pages_is_bit_exact_and_attention_follows_the_pages(hb, oracle, Hq, Hkv, D):
     """A request's pages move to another pool (bit for bit, nothing else touched); attention through the

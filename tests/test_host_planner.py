@@ -95,6 +95,18 @@ def check_coverage(b, d):
         assert np.all(d["bt"][reqs["bt_start"][r] + n:reqs["bt_start"][r] + m] == b.bt_pages[b.bt_indptr[r] + n - 1])
     qi = b.q_indptr()
     assert np.array_equal(reqs["q_start"], qi[:-1])
+    # append runs: every new token exactly once, in its page and slot, never across a page boundary
+    where = {}
+    for row0, n, page, slot0 in d["runs"]:
+        assert 1 <= n <= 16 and 0 <= slot0 and slot0 + n <= 16
+        for k in range(n):
+            assert row0 + k not in where
+            where[row0 + k] = (page, slot0 + k)
+    assert len(where) == h.total_q
+    for r in range(b.num_requests):
+        for i in range(int(b.q_len[r])):
+            t = int(b.ctx_len[r]) - int(b.q_len[r]) + i
+            assert where[qi[r] + i] == (int(b.bt_pages[b.bt_indptr[r] + t // 16]), t % 16)
     slot_owner = np.zeros(max(1, h.n_partial_rows), np.int32)
     group_count = np.zeros(max(1, h.n_groups), np.int32)
     for r in range(b.num_requests):
