@@ -133,6 +133,12 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       pages_per = (q.n_pages + nsplit - 1) / nsplit;
       pages_per += pages_per & 1;
       nsplit = (int)((q.n_pages + pages_per - 1) / pages_per);
+      HfxItem proto;                  // what all items of the request share
+      std::memset(&proto, 0, sizeof proto);
+      proto.type = HFX_ITEM_DECODE;
+      proto.req = r;
+      proto.hn = ngc;
+      proto.rq = q;
       for (int g0 = 0; g0 < Hkv; g0 += ngc) {
         int group = -1;
         if (nsplit > 1) {
@@ -141,19 +147,14 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
           P.groups.push_back(gr);
         }
         for (int s = 0; s < nsplit; ++s) {
-          HfxItem it;
-          std::memset(&it, 0, sizeof it);
-          it.type = HFX_ITEM_DECODE;
-          it.req = r;
+          HfxItem it = proto;
           it.group = group;
           it.slot_row = (nsplit > 1) ? (int32_t)(rows + (int64_t)s * ngc * G) : -1;
           it.h0 = g0;
-          it.hn = ngc;
           it.kb = (int32_t)(s * pages_per);
           it.ke = (int32_t)std::min<int64_t>(q.n_pages, (int64_t)(s + 1) * pages_per);
           int64_t toks = std::min<int64_t>(q.ctx_len, (int64_t)it.ke * HFX_PAGE) - (int64_t)it.kb * HFX_PAGE;
           it.cost = clamp_cost((double)toks * ns_per_token + 2000.0);
-          it.rq = q;
           P.items.push_back(it);
         }
         if (nsplit > 1) rows += (int64_t)nsplit * ngc * G;
@@ -176,6 +177,14 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
           const int64_t kb = s * tiles_per * HFX_KEY_TILE, ke = std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
           split_cost[(size_t)s] = clamp_cost(4.0 * D * hpw * (double)pairs_in(p, r0, r1, kb, ke) / kPrefillFlopsPerNs + 3000.0);
         }
+        HfxItem proto;                // what all items of the row tile share
+        std::memset(&proto, 0, sizeof proto);
+        proto.type = HFX_ITEM_PREFILL;
+        proto.req = r;
+        proto.hn = hpw;
+        proto.row0 = (int32_t)r0;
+        proto.nrows = rows_wg;
+        proto.rq = q;
         for (int g = 0; g < Hkv; ++g)
           for (int hb = 0; hb < G / hpw; ++hb) {
             int group = -1;
@@ -185,20 +194,13 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
               P.groups.push_back(gr);
             }
             for (int64_t s = 0; s < nsplit; ++s) {
-              HfxItem it;
-              std::memset(&it, 0, sizeof it);
-              it.type = HFX_ITEM_PREFILL;
-              it.req = r;
+              HfxItem it = proto;
               it.group = group;
               it.slot_row = (nsplit > 1) ? (int32_t)(rows + s * 4 * HFX_WAVE_ROWS) : -1;
               it.h0 = g * G + hb * hpw;
-              it.hn = hpw;
-              it.row0 = (int32_t)r0;
-              it.nrows = rows_wg;
               it.kb = (int32_t)(s * tiles_per * HFX_KEY_TILE);
               it.ke = (int32_t)std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
               it.cost = split_cost[(size_t)s];
-              it.rq = q;
               P.items.push_back(it);
             }
             if (nsplit > 1) rows += nsplit * 4 * HFX_WAVE_ROWS;
@@ -216,9 +218,13 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     key.resize(2 * n);
     uint64_t* a = key.data();
     uint64_t* b = a + n;
+    // keys count down from the largest cost, so that the number of digit passes follows the range
+    // of costs in the step and not the width of the field
+    uint32_t max_cost = 0;
+    for (size_t i = 0; i < n; ++i) max_cost = std::max(max_cost, (uint32_t)P.items[i].cost);
     uint32_t top = 0;
     for (size_t i = 0; i < n; ++i) {
-      const uint32_t inv = 0x7fffffffu - (uint32_t)P.items[i].cost;
+      const uint32_t inv = max_cost - (uint32_t)P.items[i].cost;
       a[i] = ((uint64_t)inv << 32) | (uint64_t)i;
       top |= inv;
     }
@@ -234,8 +240,9 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       for (size_t i = 0; i < n; ++i) b[count[(a[i] >> (32 + shift)) & 2047u]++] = a[i];
       std::swap(a, b);
     }
-    std::vector<HfxItem>& sorted = P.sort_tmp;
-    sorted.resize(n);
+    // the queue order is kept as a permutation; the records are put in that order when the blob is written
+    std::vector<uint32_t>& order = P.order;
+    order.resize(n);
     if (dec_ns > pre_ns && pre_ns > 0.0) {
       // A step whose decode work outweighs its prefill work.  The first two items of workgroup b
       // are queue positions b and b + HFX_PLAN_WGS, and workgroups b and b + HFX_PLAN_WGS/2 share a
@@ -263,17 +270,16 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       for (int round = 0; round < 2; ++round)
         for (size_t b = 0; b < (size_t)HFX_PLAN_WGS && o < n; ++b) {
           const bool prefill_slot = (b % kBlockItems) < pair_cus;
-          if ((prefill_slot && pi < pre.size()) || di >= dec.size()) sorted[o++] = P.items[pre[pi++]];
-          else sorted[o++] = P.items[dec[di++]];
+          if ((prefill_slot && pi < pre.size()) || di >= dec.size()) order[o++] = pre[pi++];
+          else order[o++] = dec[di++];
         }
       while (di < dec.size() || pi < pre.size()) {
-        for (size_t k = 0; k < kBlockItems && di < dec.size(); ++k) sorted[o++] = P.items[dec[di++]];
-        for (size_t k = 0; k < kBlockItems && pi < pre.size(); ++k) sorted[o++] = P.items[pre[pi++]];
+        for (size_t k = 0; k < kBlockItems && di < dec.size(); ++k) order[o++] = dec[di++];
+        for (size_t k = 0; k < kBlockItems && pi < pre.size(); ++k) order[o++] = pre[pi++];
       }
     } else {
-      for (size_t i = 0; i < n; ++i) sorted[i] = P.items[(size_t)(a[i] & 0xffffffffu)];
+      for (size_t i = 0; i < n; ++i) order[i] = (uint32_t)(a[i] & 0xffffffffu);
     }
-    P.items.swap(sorted);
   }
   // merge work units: groups with many splits get 8 threads per (row, column) and one row per
   // workgroup, groups with few splits one thread per (row, column) and 8 rows per workgroup
@@ -371,7 +377,9 @@ hfx_status fill_blob(const hfx_shape* shape, Plan& P, const int32_t* bt_indptr, 
     for (int i = q.n_pages; i < q.bt_len; ++i) dst[i] = dst[q.n_pages - 1];
   }
   put(h.off_bt + 4ull * (uint64_t)P.n_bt, nullptr, 0, h.off_items);
-  put(h.off_items, P.items.data(), sizeof(HfxItem) * P.items.size(), h.off_groups);
+  HfxItem* queue = (HfxItem*)(base + h.off_items);
+  for (size_t i = 0; i < P.items.size(); ++i) queue[i] = P.items[P.order[i]];
+  put(h.off_items + sizeof(HfxItem) * P.items.size(), nullptr, 0, h.off_groups);
   put(h.off_groups, P.groups.data(), sizeof(HfxGroup) * P.groups.size(), h.off_units);
   put(h.off_units, P.units.data(), sizeof(HfxUnit) * P.units.size(), h.off_runs);
   // append runs: each request's new tokens, cut at page boundaries

@@ -17,7 +17,7 @@ struct Plan {
   int32_t total_q = 0, n_bt = 0, n_partial_rows = 0, n_decode_items = 0, n_prefill_items = 0, n_runs = 0;
   // scratch of plan_step, kept so that a reused Plan allocates nothing once it has grown
   std::vector<uint64_t> sort_keys;
-  std::vector<HfxItem> sort_tmp;
+  std::vector<uint32_t> order;          // queue position -> index into items
   std::vector<int32_t> split_cost;
   std::vector<uint32_t> order_dec, order_pre;
 };
