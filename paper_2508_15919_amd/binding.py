@@ -344,7 +344,7 @@ class DeviceStep:
         self.workspace_bytes = wb
         self._pool = pool_dev if pool_dev is not None else torch.from_numpy(batch.pool.view(np.int16)).to(self.device)
         self.q = torch.from_numpy(batch.q.view(np.int16)).to(self.device)
-        self.out = torch.zeros_like(self.q)
+        self.out = torch.full_like(self.q, 0x7FC0)      # bf16 NaN: a row no kernel writes shows up in any compare
         self._lib = load()
         self._keep = [_i32(a) for a in (batch.kind, batch.q_len, batch.ctx_len, batch.bt_indptr, batch.bt_pages)]
         self._build_args = (ctypes.byref(self.shape), len(self._keep[0][0]), *(p for _, p in self._keep),
