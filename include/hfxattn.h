@@ -188,6 +188,31 @@ hfx_status hfx_mixed_paged_attention(const hfx_shape* shape, const void* q,
                                      void* stream);
 
 /*
+ * hfx_mixed_paged_attention for callers that cannot allocate device memory or
+ * carry a workspace of their own: code under stream capture, tight serving
+ * loops, harnesses that forbid allocation.  Same inputs, same kernels and same
+ * result bits as hfx_mixed_paged_attention, but the split partials go to a
+ * fixed workspace that lives inside the library's code object: 64 MiB
+ * (67108864 bytes) per GPU, held from the library's first use on that GPU
+ * until the process ends.  A step whose device_workspace_bytes (as
+ * hfx_batch_desc_sizes reports it) exceeds that returns HFX_ERR_BUFSIZE and
+ * enqueues nothing.
+ *
+ * The call allocates and frees nothing and calls no allocating routine; its
+ * first call on a device looks the workspace's device address up once and
+ * keeps it.  The workspace needs no clearing between calls (every partial a
+ * merge reads was written by the same call first).  All calls on one GPU share
+ * that one workspace: two of them, or one of them and nothing else that uses it,
+ * must not overlap in time on that GPU (calls on one stream never do; calls on
+ * different streams race).  hfx_mixed_paged_attention with a caller-owned
+ * workspace is not affected and may overlap with it.
+ * Errors: those of hfx_mixed_paged_attention.
+ */
+hfx_status hfx_mixed_paged_attention_static(const hfx_shape* shape, const void* q,
+                                            const void* kv_pool, const void* host_desc,
+                                            void* device_desc, void* out, void* stream);
+
+/*
  * Paging check hook: copies the keys and values of request `request`, tokens
  * [0, ctx_len), all kv-heads, out of the page pool into token-major contiguous
  * buffers, walking the same device descriptor the attention kernel walks

@@ -21,7 +21,7 @@ HFX_ERR_MODEL = -11
 HFX_DECODE, HFX_PREFILL = 0, 1
 
 EXPORTS = ["hfx_status_string", "hfx_version", "hfx_batch_desc_sizes", "hfx_build_batch_desc",
-           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_gather_kv", "hfx_append_kv",
+           "hfx_fill_batch_desc", "hfx_mixed_paged_attention", "hfx_mixed_paged_attention_static", "hfx_gather_kv", "hfx_append_kv",
            "hfx_copy_pages", "hfx_token_budget", "hfx_maturity_time", "hfx_fit_latency_model", "hfx_compose_step"]
 
 
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
         lib.hfx_build_batch_desc.restype = ctypes.c_int32
         lib.hfx_mixed_paged_attention.argtypes = [shp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
         lib.hfx_mixed_paged_attention.restype = ctypes.c_int32
+        lib.hfx_mixed_paged_attention_static.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        lib.hfx_mixed_paged_attention_static.restype = ctypes.c_int32
         lib.hfx_gather_kv.argtypes = [shp, vp, vp, vp, ctypes.c_int32, vp, vp, vp]
         lib.hfx_gather_kv.restype = ctypes.c_int32
         lib.hfx_append_kv.argtypes = [shp, vp, vp, vp, vp, vp, vp]
@@ -193,6 +195,13 @@ def hfx_mixed_paged_attention(shape: hfx_shape, q, kv_pool, host_desc, device_de
                                           _stream(stream))
     if rc != HFX_OK:
         raise HfxError(rc, "hfx_mixed_paged_attention")
+
+
+def hfx_mixed_paged_attention_static(shape: hfx_shape, q, kv_pool, host_desc, device_desc, out, stream=None) -> None:
+    rc = load().hfx_mixed_paged_attention_static(ctypes.byref(shape), _ptr(q), _ptr(kv_pool), _ptr(host_desc),
+                                                 _ptr(device_desc), _ptr(out), _stream(stream))
+    if rc != HFX_OK:
+        raise HfxError(rc, "hfx_mixed_paged_attention_static")
 
 
 def hfx_gather_kv(shape: hfx_shape, kv_pool, host_desc, device_desc, request: int, k_out, v_out,

@@ -46,6 +46,26 @@ hfx_status persistent_grid(int head_dim, int* grid) {
   return HFX_OK;
 }
 
+// The attention call proper; `h` is the descriptor's header, already checked against the shape.
+hfx_status run_attention(const HfxHeader& h, const void* q, const void* kv_pool, void* device_desc, void* workspace,
+                         size_t workspace_bytes, void* out, void* stream) {
+  hfx_status st;
+  if (h.workspace_bytes > 0 && !workspace) return HFX_ERR_NULL;
+  if (workspace_bytes < h.workspace_bytes) return HFX_ERR_BUFSIZE;
+  if (!aligned16(q) || !aligned16(kv_pool) || !aligned16(device_desc) || !aligned16(out) ||
+      (h.workspace_bytes > 0 && !aligned16(workspace)))
+    return HFX_ERR_ALIGN;
+  if (h.n_items < 1) return HFX_ERR_DESC;
+  int grid = 0;
+  st = persistent_grid(h.head_dim, &grid);
+  if (st != HFX_OK) return st;
+  if (grid > h.n_items) grid = h.n_items;
+  if (hfx::launch_mixed_attention(h, grid, device_desc, q, kv_pool, workspace, out, static_cast<hipStream_t>(stream)) !=
+      hipSuccess)
+    return HFX_ERR_DEVICE;
+  return HFX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -130,20 +150,20 @@ hfx_status hfx_mixed_paged_attention(const hfx_shape* shape, const void* q, cons
   HfxHeader h;
   hfx_status st = check_header(shape, host_desc, &h);
   if (st != HFX_OK) return st;
-  if (h.workspace_bytes > 0 && !workspace) return HFX_ERR_NULL;
-  if (workspace_bytes < h.workspace_bytes) return HFX_ERR_BUFSIZE;
-  if (!aligned16(q) || !aligned16(kv_pool) || !aligned16(device_desc) || !aligned16(out) ||
-      (h.workspace_bytes > 0 && !aligned16(workspace)))
-    return HFX_ERR_ALIGN;
-  if (h.n_items < 1) return HFX_ERR_DESC;
-  int grid = 0;
-  st = persistent_grid(h.head_dim, &grid);
+  return run_attention(h, q, kv_pool, device_desc, workspace, workspace_bytes, out, stream);
+}
+
+hfx_status hfx_mixed_paged_attention_static(const hfx_shape* shape, const void* q, const void* kv_pool,
+                                            const void* host_desc, void* device_desc, void* out,
+                                            void* stream) {
+  if (!q || !kv_pool || !device_desc || !out) return HFX_ERR_NULL;
+  HfxHeader h;
+  hfx_status st = check_header(shape, host_desc, &h);
   if (st != HFX_OK) return st;
-  if (grid > h.n_items) grid = h.n_items;
-  if (hfx::launch_mixed_attention(h, grid, device_desc, q, kv_pool, workspace, out, static_cast<hipStream_t>(stream)) !=
-      hipSuccess)
-    return HFX_ERR_DEVICE;
-  return HFX_OK;
+  if (h.workspace_bytes > (uint64_t)HFX_STATIC_WS_BYTES) return HFX_ERR_BUFSIZE;
+  void* ws = nullptr;
+  if (hfx::static_workspace(&ws) != hipSuccess) return HFX_ERR_DEVICE;
+  return run_attention(h, q, kv_pool, device_desc, ws, (size_t)HFX_STATIC_WS_BYTES, out, stream);
 }
 
 hfx_status hfx_gather_kv(const hfx_shape* shape, const void* kv_pool, const void* host_desc,

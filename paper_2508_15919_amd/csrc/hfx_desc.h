@@ -12,6 +12,9 @@
 #define HFX_BT_PAD 16            /* stored block-table entries after a request's last page, all naming that page */
 #define HFX_WAVE_ROWS 32         /* query rows one wavefront owns in a prefill item (one MFMA row block) */
 
+#define HFX_STATIC_WS_BYTES (64u << 20) /* fixed workspace of the entry point that allocates nothing */
+#define HFX_MAX_DEVICES 64
+
 enum { HFX_ITEM_DECODE = 0, HFX_ITEM_PREFILL = 1 };
 
 struct HfxHeader {

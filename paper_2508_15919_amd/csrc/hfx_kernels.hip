@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "hfx_desc.h"
 #include "hfx_launch.h"
 
@@ -1135,6 +1137,31 @@ __global__ __launch_bounds__(D) void append_kv_kernel(const HfxRun* __restrict__
         dst[b] = sv[(b - lo) * LD + d];
     }
   }
+}
+
+// ------------------------------------------------------------------ static workspace
+// Split partials for callers that cannot allocate device memory: a fixed array inside the code
+// object, one copy per GPU, held until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; the device address it yields (per device) is what launches get.
+static __device__ __align__(256) unsigned char scratch[HFX_STATIC_WS_BYTES];
+
+hipError_t static_workspace(void** ptr) {
+  static std::mutex mu;
+  static void* addr[HFX_MAX_DEVICES];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= HFX_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
 }
 
 // ------------------------------------------------------------------ host-side launch helpers

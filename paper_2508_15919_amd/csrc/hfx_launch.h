@@ -9,6 +9,9 @@ namespace hfx {
 hipError_t max_resident_workgroups(int head_dim, int* per_cu);
 hipError_t launch_mixed_attention(const HfxHeader& header, int grid, void* desc, const void* q, const void* pool,
                                   void* ws, void* out, hipStream_t stream);
+// Device address, on the current device, of the library's fixed workspace of HFX_STATIC_WS_BYTES
+// (looked up once per device, then cached).
+hipError_t static_workspace(void** ptr);
 hipError_t launch_gather_kv(const void* desc, const void* pool, int request, long elements, void* k_out,
                             void* v_out, hipStream_t stream);
 
