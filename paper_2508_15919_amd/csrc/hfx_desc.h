@@ -8,7 +8,8 @@
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
-#define HFX_KEY_TILE 64          /* keys per prefill tile (4 pages) */
+#define HFX_KEY_TILE 64          /* key ranges of prefill items start at multiples of this */
+#define HFX_STAGE_KEYS 32        /* keys per prefill pipeline stage (2 pages) */
 #define HFX_BT_PAD 16            /* stored block-table entries after a request's last page, all naming that page */
 #define HFX_WAVE_ROWS 32         /* query rows one wavefront owns in a prefill item (one MFMA row block) */
 

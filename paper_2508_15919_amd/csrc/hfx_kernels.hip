@@ -32,13 +32,18 @@ struct KArgs {
 
 template <int D>
 struct Smem {
-  // prefill: K tiles of 64 keys in operand order ([D/16][2][2][32 keys][8 dims]); three of them rotate
-  static constexpr int kKBytes = HFX_KEY_TILE * D * 2;
-  static constexpr int kKBuffers = 3;
+  // prefill: two stage buffers of 32 keys (two pages) each, the halves of a 64-key tile.  A stage holds the keys in
+  // operand order ([D/16][2 dimension halves][32 keys][8 dims], 1 KB per 16-dimension group) followed by
+  // the two pages' V blocks as they lie in the pool ([D dims][16 slots] each).
+  static constexpr int kKBytes = HFX_STAGE_KEYS * D * 2;
+  static constexpr int kPageVBytes = HFX_PAGE * D * 2;
+  static constexpr int kStageBytes = kKBytes + 2 * kPageVBytes;
+  static constexpr int kStages = 2;
+  static constexpr int kCopies = D / 32;         // 16-byte pieces per lane that a wavefront moves per stage
   // decode: per-wavefront partial rows [4][16][D + 4] floats (same memory; an item is one or the other)
   static constexpr int kPartStride = D + 4;
   static constexpr int kPartBytes = 4 * 16 * kPartStride * 4;
-  static constexpr int kBytes = kKBuffers * kKBytes > kPartBytes ? kKBuffers * kKBytes : kPartBytes;
+  static constexpr int kBytes = kStages * kStageBytes > kPartBytes ? kStages * kStageBytes : kPartBytes;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -55,9 +60,35 @@ __device__ __forceinline__ float keep_or_neg_inf(float x, bool keep) {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// Exchange between lane n and lane n ^ 32.
-__device__ __forceinline__ float max_xor32(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
-__device__ __forceinline__ float sum_xor32(float x) { return x + __shfl_xor(x, 32, 64); }
+// Exchange between lane n and lane n ^ 32 with the swap instruction gfx950 has for it (the upper half
+// of one register against the lower half of another); a shuffle would go through LDS and put
+// its latency, and a wait for every LDS read in flight, into the softmax of every stage.
+// swap32(x): {x of the lower-half lane of the pair, x of its upper-half lane}, in both lanes.
+// The copies in and out are hidden from the optimizer, which otherwise folds the swap of a value
+// with itself, and whatever combines its two results, into the value.
+struct Pair32 {
+  float lo, hi;
+};
+__device__ __forceinline__ Pair32 swap32(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  unsigned u2 = u;
+  asm volatile("" : "+v"(u2));
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u2, false, false);
+  unsigned a = r[0], b = r[1];
+  asm volatile("" : "+v"(a), "+v"(b));
+  Pair32 p;
+  p.lo = __builtin_bit_cast(float, a);
+  p.hi = __builtin_bit_cast(float, b);
+  return p;
+}
+__device__ __forceinline__ float max_xor32(float x) {
+  const Pair32 p = swap32(x);
+  return fmaxf(p.lo, p.hi);
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  const Pair32 p = swap32(x);
+  return p.lo + p.hi;
+}
 
 // zero the elements e >= nv of an 8-element bf16 vector (nv may be <= 0 or >= 8)
 __device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int nv) {
@@ -475,101 +506,82 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
 
 // ----------------------------------------------------------------------------------------------
 // Prefill item.  Four wavefronts, each owning 32 chunk rows of one q-head; all four share the
-// kv-head.  On CDNA4 this loop is bounded by operand delivery (an LDS read or a vector-memory
-// load of a 1 KB MFMA operand costs about 16 cycles of its unit per CU, an MFMA 32x32x16 takes
-// 32 cycles of one of four SIMDs), so the two contractions take their tiles over two paths:
-//   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows from an LDS tile that the workgroup fills
-//                                                 once per 64 keys with direct-to-LDS loads (three
-//                                                 buffers; the page's K block is already in operand
-//                                                 order), B = Q^T in registers;
-//   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows loaded straight from the page pool (a
-//                                                 dimension-major V block is the operand layout),
-//                                                 B = P^T from the score registers.
+// kv-head.  Both contractions take their streamed operand from LDS, which on CDNA4 delivers 16-byte
+// reads at about 256 bytes per clock and CU, four times what the vector-memory path gives a wavefront
+// (about 64 bytes per clock and CU, measured): with 32 rows per wavefront every MFMA 32x32x16 needs a
+// fresh 1 KB operand, 128 bytes per clock and CU at full matrix rate.
+//   S^T[key][row]  = K[key][:] . Q[row][:]        A = K rows out of the stage buffer, B = Q^T in registers;
+//   O^T[d][row]   += V^T[d][key] . P^T[key][row]  A = V^T rows out of the stage buffer (a dimension-major
+//                                                 V block is the operand layout), B = P^T from the
+//                                                 score registers.
+// The workgroup fills a stage (32 keys: two pages' K and V blocks, 16 KB at D = 128) once with
+// direct-to-LDS loads, two stages ahead of the one being multiplied; the global-to-LDS traffic is a
+// quarter of what four wavefronts loading their own fragments would move.
 // Each lane owns one query row (a column of S^T and O^T), so the running maximum, sum and rescale
 // are lane-local up to one exchange with lane ^ 32.  The K rows of a score tile are taken in the
 // order that leaves every lane with 8 consecutive keys of one page per 16-key MFMA step.
 // ----------------------------------------------------------------------------------------------
-struct TilePages {
-  int pg[4];
+struct StagePages {     // the two pages of a 32-key stage
+  int pg0, pg1;
 };
 
-// bt: the step's whole stored block table; bt0: where the request's entries start (a multiple
-// of 4); kt: first key of the tile (a multiple of 64).  The stored table repeats the last page for
-// HFX_BT_PAD entries behind each request, so the quad needs no clamping up to three tiles past the end.
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ TilePages tile_pages(const int* __restrict__ bt, int bt0, int kt) {
-  const i32x4 v = *reinterpret_cast<const i32x4*>(bt + bt0 + kt / HFX_PAGE);
-  TilePages t;
-  t.pg[0] = v[0];
-  t.pg[1] = v[1];
-  t.pg[2] = v[2];
-  t.pg[3] = v[3];
-  return t;
-}
-
-// Asynchronous copy of one 64-key K tile into `kbuf`, laid out [D/16][2 key halves][2 dimension
-// halves][32 keys][8 dims].  One direct-to-LDS instruction moves 1 KB: the 32-byte pieces of 32
-// keys (two pages) for one 16-dimension group; the (D/16)*2 instructions of a tile are dealt out over the four wavefronts.
-template <int D>
-__device__ __forceinline__ void k_tile_async(char* kbuf, const __bf16* pool, const TilePages& tp, int Hkv, int g,
-                                             int wave, int lane) {
-  constexpr int kPerWave = (D / 16) * 2 / 4;       // 4 (D = 128) or 2 (D = 64) copies per wavefront
-  constexpr long kBlock = 16 * D;
-  // A wavefront's copies are q = wave * kPerWave + i: dimension group kk = q >> 1, key half kh = q & 1.
-  // The K-block addresses of the tile's four pages are formed in scalar registers; a lane then only
-  // picks the page of its key (lanes 16-31 and 48-63 hold the second page of a half) and adds its
-  // own offset; copies that differ only in kk use the instruction's immediate offset.
-  auto k_block = [&](int pg) { return reinterpret_cast<uintptr_t>(pool + (((long)pg * Hkv + g) * 2) * kBlock); };
-  const bool second = (lane >> 4) & 1;
-  const int kk0 = (wave * kPerWave) >> 1;
-  // lane l fills LDS slot l of the 1 KB block: slot = 32 * (dimension half) + key, so that the 16
-  // lanes the LDS serves together later read 16 different bank groups
-  const unsigned lane_bytes = (unsigned)(((kk0 * 16 + (lane & 15)) * 16 + (lane >> 5) * 8) * 2);
-#pragma unroll
-  for (int kh = 0; kh < 2; ++kh) {
-    const uintptr_t first_page = k_block(kh ? tp.pg[2] : tp.pg[0]), second_page = k_block(kh ? tp.pg[3] : tp.pg[1]);
-    const char* src = reinterpret_cast<const char*>((second ? second_page : first_page) + lane_bytes);
-#pragma unroll
-    for (int dk = 0; dk < kPerWave / 2; ++dk) {
-      char* dst = kbuf + (kk0 + dk) * (HFX_KEY_TILE * 32) + kh * 1024;
-      // Issued as inline assembly on purpose: the compiler's wait-count pass treats its own
-      // direct-to-LDS intrinsic as aliasing every later LDS read and drains the whole vector-memory
-      // queue in front of them, which would stall the V stream on every tile.  Here the copy is
-      // ordered by hand: the caller waits for vmcnt(0) and crosses a barrier before the tile is read.
-      const unsigned lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)dst;
-      if (dk == 0)
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "m0", "memory");
-      else   // the immediate offset moves the LDS address along with the global one: take it off again
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:512"
-                     :
-                     : "v"(src), "s"(lds - 512u)
-                     : "m0", "memory");
-    }
-  }
-}
-
-template <int D>
-struct VHalf {
-  bf16x8 f[2][D / 32];     // V^T operand fragments of 32 keys: [page][32-dimension block]
-  static constexpr int kLoads = 2 * (D / 32);
+// What a lane contributes to every stage copy; fixed for the lifetime of the kernel.  Wavefronts 0
+// and 1 copy the keys (D/32 groups of 16 dimensions each: 1 KB per instruction, the 32-byte pieces of
+// 32 keys, lanes 16-31 and 48-63 taking the second page), wavefronts 2 and 3 copy the V block of the
+// first and of the second page (1 KB per instruction, as it lies).
+struct CopyLane {
+  unsigned src_off;    // byte offset of the lane's first piece inside the (page, kv-head) K|V block pair
+  unsigned lds_off;    // where the wavefront's pieces start inside a stage buffer
+  bool second;         // the lane reads the stage's second page
 };
 
-// vh.f[sp][b] = V^T rows 32b+n, keys 8j.. of page pg_sp, loaded straight from the pool
 template <int D>
-__device__ __forceinline__ void v_half_load(VHalf<D>& vh, const __bf16* pool, int pg0, int pg1, int Hkv, int g,
-                                            int v_lane) {
-  constexpr long kBlock = 16 * D;
-#pragma unroll
-  for (int sp = 0; sp < 2; ++sp) {
-    // The V block starts 4096 bytes into the (page, kv-head) block, one more than a load's immediate
-    // offset can hold.  Left visible, the compiler peels that constant off the scalar block address
-    // and adds it back per lane, twice; the empty asm keeps the scalar sum in one piece.
-    long block = (((long)(sp ? pg1 : pg0) * Hkv + g) * 2 + 1) * kBlock;
-    asm volatile("" : "+s"(block));
-    const __bf16* vb = pool + block + v_lane;
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b) vh.f[sp][b] = ld16(vb + b * 512);
+__device__ __forceinline__ CopyLane copy_lane(int wave, int lane) {
+  CopyLane c;
+  if (wave < 2) {
+    const int kk0 = wave * Smem<D>::kCopies;
+    // lane l fills LDS slot l of a 1 KB group: slot = 32 * (dimension half) + key, so that the 16
+    // lanes the LDS serves together later read 16 different bank groups
+    c.src_off = (unsigned)(((kk0 * 16 + (lane & 15)) * 16 + (lane >> 5) * 8) * 2);
+    c.lds_off = (unsigned)(kk0 * 1024);
+    c.second = (lane >> 4) & 1;
+  } else {
+    c.src_off = (unsigned)(HFX_PAGE * D * 2 + lane * 16);
+    c.lds_off = (unsigned)(Smem<D>::kKBytes + (wave - 2) * Smem<D>::kPageVBytes);
+    c.second = wave == 3;
   }
+  return c;
+}
+
+// A wavefront's share of one 32-key stage on its way from the pool to LDS: D/32 pieces of 16 bytes per lane.
+template <int D>
+struct StageRegs {
+  u32x4 r[Smem<D>::kCopies];
+};
+
+// Requests this wavefront's pieces of the stage made of pages pg0, pg1 of kv-head g.
+template <int D>
+__device__ __forceinline__ void stage_load(StageRegs<D>& sr, const __bf16* pool, const StagePages& sp, int Hkv, int g,
+                                           const CopyLane& cl, int wave) {
+  constexpr long kPairBytes = 2L * HFX_PAGE * D * 2;   // K block + V block of one (page, kv-head)
+  // the block addresses of the two pages are formed in scalar registers; a lane only picks its page
+  const uintptr_t b0 = reinterpret_cast<uintptr_t>(pool) + ((long)sp.pg0 * Hkv + g) * kPairBytes;
+  const uintptr_t b1 = reinterpret_cast<uintptr_t>(pool) + ((long)sp.pg1 * Hkv + g) * kPairBytes;
+  // (an address formed from integers has to be told that it is a global one, or the loads come out as flat loads)
+  typedef const __attribute__((address_space(1))) char* gptr;
+  gptr src = reinterpret_cast<gptr>((cl.second ? b1 : b0) + cl.src_off);
+  const int step = wave < 2 ? 512 : 1024;   // keys: the next 16-dimension group is 512 bytes on in the page; values: 1 KB
+#pragma unroll
+  for (int i = 0; i < Smem<D>::kCopies; ++i)
+    sr.r[i] = *reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(src + i * step);
+}
+
+// ... and puts them into the stage buffer `buf` (1 KB per instruction, lane l at 16 l).
+template <int D>
+__device__ __forceinline__ void stage_write(char* buf, const StageRegs<D>& sr, const CopyLane& cl, int lane) {
+  char* dst = buf + cl.lds_off + lane * 16;
+#pragma unroll
+  for (int i = 0; i < Smem<D>::kCopies; ++i) *reinterpret_cast<u32x4*>(dst + i * 1024) = sr.r[i];
 }
 
 // Per-wavefront state of a prefill item that lives across key tiles.
@@ -627,26 +639,24 @@ __device__ __forceinline__ void softmax_block(f32x16& s, PrefillWave<D>& w, bf16
   w.l += ps;
 }
 
+// One 32-key stage out of the LDS buffer `buf` against the wavefront's 32 rows; key0 is the stage's
+// first key.  k_lane / v_lane: byte offsets of this lane's K row and V^T fragment inside the buffer.
 template <int D>
-struct KFrags {
-  bf16x8 f[D / 16];        // K operand fragments of 32 keys, one per 16-dimension group
-};
-
-// kb points at this lane's K row of a 32-key half inside the LDS tile
-template <int D>
-__device__ __forceinline__ void k_frags_read(KFrags<D>& kf, const char* kb) {
+__device__ __forceinline__ void prefill_stage(PrefillWave<D>& w, const char* buf, int k_lane, int v_lane, bool masked,
+                                              bool past_ctx, int key0, int ctx_len, int j, float sl2, char* fill,
+                                              const StageRegs<D>& sr, const CopyLane& cl, int lane) {
+  bf16x8 kf[D / 16];
+  bf16x8 vf[2][D / 32];
 #pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk)
-    kf.f[kk] = *reinterpret_cast<const bf16x8*>(kb + kk * (HFX_KEY_TILE * 32));
+  for (int kk = 0; kk < D / 16; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(buf + kk * 1024 + k_lane);
+#pragma unroll
+  for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+      vf[sp][b] = *reinterpret_cast<const bf16x8*>(buf + Smem<D>::kKBytes + sp * Smem<D>::kPageVBytes + b * 1024 + v_lane);
   // keep all the reads in front of the MFMA chain that consumes them: left alone, the scheduler
-  // sinks each read next to its MFMA to save registers and exposes the LDS latency eight times
+  // sinks each read next to its MFMA to save registers and exposes the LDS latency every time
   __builtin_amdgcn_sched_barrier(0);
-}
-
-// 32 keys (two pages) against the wavefront's 32 rows; key0 is the first key of the half.
-template <int D>
-__device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, const KFrags<D>& kf, bool masked,
-                                             bool past_ctx, int key0, int ctx_len, int j, float sl2) {
   f32x16 s;
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
@@ -654,17 +664,20 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
       f32x16 z;
 #pragma unroll
       for (int v = 0; v < 16; ++v) z[v] = 0.f;
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.f[kk], w.qf[kk], z, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], w.qf[kk], z, 0, 0, 0);
     } else {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.f[kk], w.qf[kk], s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], w.qf[kk], s, 0, 0, 0);
     }
   }
-  if (past_ctx) {              // the half runs past the context: unused V slots may hold anything
+  // the pieces of the stage after next go to the other buffer while the score MFMAs run
+  stage_write<D>(fill, sr, cl, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  if (past_ctx) {              // the stage runs past the context: unused V slots may hold anything
     asm volatile("" ::: );
 #pragma unroll
     for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
-      for (int b = 0; b < D / 32; ++b) vh.f[sp][b] = keep_first(vh.f[sp][b], ctx_len - (key0 + sp * 16 + j * 8));
+      for (int b = 0; b < D / 32; ++b) vf[sp][b] = keep_first(vf[sp][b], ctx_len - (key0 + sp * 16 + j * 8));
   }
   bf16x8 pb[2];
   softmax_block<D>(s, w, pb, sl2, masked, key0 + j * 8);
@@ -672,7 +685,7 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
   for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
     for (int b = 0; b < D / 32; ++b)
-      w.o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh.f[sp][b], pb[sp], w.o[b], 0, 0, 0);
+      w.o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[sp][b], pb[sp], w.o[b], 0, 0, 0);
 }
 
 // s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
@@ -683,73 +696,39 @@ __device__ __forceinline__ void prefill_half(PrefillWave<D>& w, VHalf<D>& vh, co
 struct TileStream {
   int bt0;            // start of the current item's request in the stored block table
   int g;              // kv-head
-  int end;            // first key past the current item's last (whole) tile
+  int end;            // first key past the current item's last (whole) 64-key tile
   bool next_ok;
-  int bt0_n, g_n, kb_n;   // the same for the next item, and its first key
+  int bt0_n, g_n, kb_n, len_n;   // the same for the next item, its first key and its length in whole tiles' keys
 };
 
-// Pages of the 64-key tile that starts `kt` keys into the stream (kt counts on past the end of
-// the current item into the next one's range; with no next prefill item it reads on in the
-// current request's stored table, whose padding repeats the last page, and the data is never used).
-__device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, const TileStream& ts, int kt,
-                                                  int& g_out) {
-  const bool into_next = kt >= ts.end && ts.next_ok;
-  const int bt0 = into_next ? ts.bt0_n : ts.bt0;
-  const int k = into_next ? ts.kb_n + (kt - ts.end) : kt;
-  g_out = into_next ? ts.g_n : ts.g;
-  return tile_pages(bt, bt0, k);
-}
+// Page ids of the 64-key tile that starts `kt` keys into a request (kt a multiple of 64): one aligned
+// quad out of the step's stored block table.  The stored table repeats a request's last page for
+// HFX_BT_PAD entries behind it, so the quad needs no clamping a tile past the end.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+struct TilePages {
+  StagePages half[2];
+};
 
-// One 64-key tile from the LDS buffer `kcur`.  Order of the memory traffic: the V fragments of
-// the second half are requested first; once the last K operands of this tile have been read out
-// of LDS, the V fragments of the next tile's first half are requested and the copy of the K tile
-// two tiles ahead goes into `kfill` (three buffers rotate, so the buffer being filled was last
-// read one tile ago and every wavefront has passed a barrier since).  "Next" and "two ahead" are
-// positions in the workgroup's tile stream: past the end of the item they are the first tiles of
-// the next prefill item.  Loads return in order: by the time this tile's second-half V fragments
-// have arrived, the K tile requested one tile earlier has landed too, so the barrier at the end
-// needs no wait of its own.
-template <int D>
-__device__ __forceinline__ void prefill_tile(PrefillWave<D>& w, TilePages& tp, TilePages& tn, int& gn, VHalf<D>& vx,
-                                             VHalf<D>& vy,
-                                             const char* kcur, char* kfill, const __bf16* pool,
-                                             const int* __restrict__ bt, const TileStream& ts, int kt, int wave_kend, int wave_pmin,
-                                             int ctx_len, int Hkv, int k_lane, int v_lane, int j, float sl2,
-                                             int wave, int lane, bool publish, bool reserve, Tickets& t, int* s_tk,
-                                             int* ctrl) {
-  const bool active = kt < wave_kend;
-  const bool masked = kt + HFX_KEY_TILE - 1 > wave_pmin;
-  const bool past_ctx = kt + HFX_KEY_TILE > ctx_len;
-  // Every load below is issued unconditionally (past the end of the stream the stored block table
-  // repeats the request's last page, so the addresses stay valid and the data is simply not used): the wait counters the
-  // compiler derives are compile-time constants, and a path that skipped a load would force
-  // them to zero and stall the pipeline on every tile.
-  KFrags<D> kf;
-  v_half_load<D>(vy, pool, tp.pg[2], tp.pg[3], Hkv, ts.g, v_lane);
-  k_frags_read<D>(kf, kcur + k_lane);
-  if (active) prefill_half<D>(w, vx, kf, masked, past_ctx, kt, ctx_len, j, sl2);
-  k_frags_read<D>(kf, kcur + 1024 + k_lane);
-  // tn, gn: pages and kv-head of the stream's next tile, looked up one tile ago
-  v_half_load<D>(vx, pool, tn.pg[0], tn.pg[1], Hkv, gn, v_lane);
-  tp = tn;
-  // The copy goes last: the compiler does not count it, so the waits it derives for the V
-  // fragments above would otherwise also wait for a copy issued in front of them.
-  tn = stream_pages(bt, ts, kt + 2 * HFX_KEY_TILE, gn);
-  k_tile_async<D>(kfill, pool, tn, Hkv, gn, wave, lane);
-  // on the diagonal the second 32 keys may lie past every row of the wavefront
-  if (kt + 32 < wave_kend) prefill_half<D>(w, vy, kf, masked, past_ctx, kt + 32, ctx_len, j, sl2);
-  else HFX_WAIT_VMCNT(VHalf<D>::kLoads + (D / 16) * 2 / 4);   // an idle wavefront must still see its earlier copy land
-  if (publish) {
-    // The ticket asked for a tile ago (or at the last hand-over) is published ahead of this tile's
-    // barrier, so that the hand-over at the end of the item needs no barrier of its own.  It is
-    // done at the end of the tile: reading the counter's reply makes the wavefront wait for
-    // whatever it had in flight when it asked.
-    tickets_publish(t, s_tk);
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the LDS write has been performed
-  }
-  if (reserve) tickets_reserve(t, ctrl);   // after the publish in program order: never both in one tile
-  __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the copies ordered above
-  asm volatile("" ::: "memory");  // keep the next tile's LDS reads below the barrier
+// Pages and kv-head of the tile that starts `kt` keys into the stream.  The tile after an item's
+// last is the first tile of the workgroup's next item (key ranges of items start at multiples of
+// 64).  `known` says whether the position lies in the current or in the next item; past those (the
+// item after next has no ticket yet), and with no next prefill item at all, the stored table is read
+// on into its padding, which repeats a request's last page: readable pages whose data is never used.
+__device__ __forceinline__ TilePages stream_pages(const int* __restrict__ bt, const TileStream& ts, int kt,
+                                                  int& g_out, bool& known) {
+  const bool into_next = kt >= ts.end && ts.next_ok;
+  const int off = kt - ts.end;
+  known = kt < ts.end || (ts.next_ok && off < ts.len_n);
+  const int bt0 = into_next ? ts.bt0_n : ts.bt0;
+  const int k = into_next ? ts.kb_n + off : kt;
+  g_out = into_next ? ts.g_n : ts.g;
+  const i32x4 v = *reinterpret_cast<const i32x4*>(bt + bt0 + k / HFX_PAGE);
+  TilePages t;
+  t.half[0].pg0 = v[0];
+  t.half[0].pg1 = v[1];
+  t.half[1].pg0 = v[2];
+  t.half[1].pg1 = v[3];
+  return t;
 }
 
 // What a wavefront derives from a prefill item: its q-head and rows, and the key ranges that
@@ -845,25 +824,40 @@ __device__ __forceinline__ void prefill_store(const KArgs& a, const HfxHeader* H
 }
 
 // Runs the prefill item t.cur and, for as long as the workgroup's next item is a prefill item as
-// well, carries straight on into it: the tile pipeline (K copy two tiles ahead, V fragments one
-// tile ahead) does not drain between items, only the per-row state (Q, O, m, l) is swapped.
-// Returns with t.cur at the first item it did not process.
+// well, carries straight on into it: the K/V pipeline does not drain between items, only the
+// per-row state (Q, O, m, l) is swapped.  Returns with t.cur at the first item it did not process.
+//
+// The pipeline, per 64-key tile (two stages, buffers 0 and 1):
+//   first stage  : request the next tile's first half from the pool into register set A; multiply
+//                  buffer 0; put register set B (this tile's second half, requested a tile ago) into
+//                  buffer 1; barrier.
+//   second stage : request the next tile's second half into register set B; multiply buffer 1; put
+//                  register set A into buffer 0; barrier.
+// Every piece therefore has two stages between its request and its use, and ordinary loads are
+// used on purpose: the direct-to-LDS form of the load moved about 16 bytes per clock and CU here,
+// a quarter of the ordinary path, and bounded the loop.  "Next tile" is a position in the
+// workgroup's tile stream: past the end of the item it is the first tile of the next prefill item.
 template <int D>
 __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* __restrict__ items, int n_items,
                             Tickets& t, int* s_tk, int* ctrl, char* smem, char* o_stage) {
+  constexpr int SK = HFX_STAGE_KEYS;
+  constexpr int SB = Smem<D>::kStageBytes;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
   const int Hq = H->num_q_heads, Hkv = H->num_kv_heads;
   const int G = Hq / Hkv;
   const int n = lane & 31, j = lane >> 5;
-  char* stage = o_stage + wave * 4096;
+  // The result rows are staged in buffer 1 at the hand-over: its stage has been multiplied, and the
+  // slice a wavefront stages its rows in is the slice that only its own next pieces go to.
+  char* stage = D == 128 ? smem + SB + wave * 4096 : o_stage + wave * 4096;
   const float sl2 = H->softmax_scale * 1.4426950408889634f;
   const int* bt_all = reinterpret_cast<const int*>(a.desc + H->off_bt);
-  // row of this lane's key inside a 32-key half of the LDS tile
+  // row of this lane's key inside the stage's 32 keys
   const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
   const int k_lane = (j * 32 + krow) * 16;
-  const int v_lane = n * 16 + j * 8;   // element offset of this lane's V^T fragment inside a V block
+  const int v_lane = (n * 2 + j) * 16;   // V^T rows 32b + n, keys 8j.. of a page: 16 bytes at (32b + n) * 32 + 16j
+  const CopyLane cl = copy_lane<D>(wave, lane);
 
   HfxItem it = items[t.cur];
   HfxItem nx = items[t.nxt < n_items ? t.nxt : t.cur];
@@ -876,11 +870,12 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     ts.bt0_n = nx.rq.bt_start;
     ts.g_n = nx.h0 / G;
     ts.kb_n = nx.kb;
+    ts.len_n = (nx.ke - nx.kb + HFX_KEY_TILE - 1) / HFX_KEY_TILE * HFX_KEY_TILE;
   };
   set_stream();
-  // Tiles (by first key) at whose end the next ticket is asked for and published: the last but
-  // two and the last but one of the item.  Items of one or two tiles ask at the hand-over and
-  // publish at the end of their first tile.
+  // Tiles (by first key) at whose start the next ticket is published and asked for: published at
+  // the last tile but one, asked for a tile earlier.  Items of one or two tiles ask at the
+  // hand-over and publish at their first tile.
   int publish_kt, reserve_kt;
   auto set_ticket_points = [&]() {
     const int n_tiles = (it.ke - it.kb + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
@@ -893,6 +888,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
 
   PrefillWave<D> w;
   WaveRows wr = wave_rows<D>(it, wave, n);
+  int wave_end = min(wr.wave_kend, it.ke);   // keys from here on: nothing to do for this wavefront
   q_load<D>(w, a, it, wr, Hq, j);
 #pragma unroll
   for (int b = 0; b < D / 32; ++b)
@@ -901,43 +897,62 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   w.m = NEG_INF;
   w.l = 0.f;
 
-  // cold start: the first two tiles of the stream and the first V fragments
+  // cold start: the first tile's first half goes to buffer 0, its second half is requested; the
+  // page ids of the tile after it are looked up (they are always asked for a tile before the loads
+  // that need them, so that no tile starts by waiting for a scalar load)
   int kt = it.kb;
-  TilePages tp = tile_pages(bt_all, ts.bt0, kt);
-  k_tile_async<D>(smem, a.pool, tp, Hkv, ts.g, wave, lane);
+  StageRegs<D> ra, rb;
+  TilePages tn;
   int gn;
-  TilePages tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
-  k_tile_async<D>(smem + Smem<D>::kKBytes, a.pool, tn, Hkv, gn, wave, lane);
-  VHalf<D> vx, vy;
-  v_half_load<D>(vx, a.pool, tp.pg[0], tp.pg[1], Hkv, ts.g, v_lane);
-  HFX_WAIT_VMCNT(0);
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  int cur = 0;   // byte offset of the K buffer holding the current tile; the one two ahead is refilled
-  bool recopy = false;
+  bool tn_known;
+  {
+    int gq;
+    bool known;
+    const TilePages tp = stream_pages(bt_all, ts, kt, gq, known);
+    stage_load<D>(ra, a.pool, tp.half[0], Hkv, gq, cl, wave);
+    stage_load<D>(rb, a.pool, tp.half[1], Hkv, gq, cl, wave);
+    tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn, tn_known);
+    stage_write<D>(smem, ra, cl, lane);
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wavefront's pieces are in LDS
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
   for (;;) {
-    if (recopy) {
-      // first tile of a one-tile item: the stream position after it belongs to an item that was
-      // not known yet when that position's copy was issued; request it again, now with the right
-      // pages.  (Issued here rather than at the hand-over: there the compiler closes the block
-      // with a wait for everything in flight, which would include this copy.)
-      int nb = cur + Smem<D>::kKBytes;
-      if (nb >= 3 * Smem<D>::kKBytes) nb = 0;
-      tn = stream_pages(bt_all, ts, kt + HFX_KEY_TILE, gn);
-      k_tile_async<D>(smem + nb, a.pool, tn, Hkv, gn, wave, lane);
-      recopy = false;
+    if (kt == publish_kt) {
+      // The ticket asked for earlier is published ahead of this tile's barriers, so that the
+      // hand-over at the end of the item needs no barrier of its own.  Reading the counter's reply
+      // makes the wavefront wait for what it had in flight when it asked.
+      tickets_publish(t, s_tk);
     }
-    int fill = cur + 2 * Smem<D>::kKBytes;
-    if (fill >= 3 * Smem<D>::kKBytes) fill -= 3 * Smem<D>::kKBytes;
-    prefill_tile<D>(w, tp, tn, gn, vx, vy, smem + cur, smem + fill, a.pool, bt_all, ts, kt, wr.wave_kend, wr.wave_pmin,
-                    it.rq.ctx_len, Hkv, k_lane, v_lane, j, sl2, wave, lane, kt == publish_kt, kt == reserve_kt, t, s_tk,
-                    ctrl);
-    cur += Smem<D>::kKBytes;
-    if (cur >= 3 * Smem<D>::kKBytes) cur = 0;
+    if (kt == reserve_kt) tickets_reserve(t, ctrl);   // never in the publishing tile
+    // ---- first stage: keys kt .. kt + 31 out of buffer 0
+    stage_load<D>(ra, a.pool, tn.half[0], Hkv, gn, cl, wave);
+    if (kt < wave_end) {
+      prefill_stage<D>(w, smem, k_lane, v_lane, kt + SK - 1 > wr.wave_pmin, kt + SK > it.rq.ctx_len, kt,
+                       it.rq.ctx_len, j, sl2, smem + SB, rb, cl, lane);
+    } else {
+      stage_write<D>(smem + SB, rb, cl, lane);
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();   // bare barrier: LDS is only written by the pieces ordered above
+    asm volatile("" ::: "memory");  // keep the next stage's LDS reads below the barrier
+    // ---- second stage: keys kt + 32 .. kt + 63 out of buffer 1
+    stage_load<D>(rb, a.pool, tn.half[1], Hkv, gn, cl, wave);
+    // the tile after next, for the next tile's loads
+    tn = stream_pages(bt_all, ts, kt + 2 * HFX_KEY_TILE, gn, tn_known);
+    if (kt + SK < wave_end) {
+      prefill_stage<D>(w, smem + SB, k_lane, v_lane, kt + 2 * SK - 1 > wr.wave_pmin, kt + 2 * SK > it.rq.ctx_len,
+                       kt + SK, it.rq.ctx_len, j, sl2, smem, ra, cl, lane);
+    } else {
+      stage_write<D>(smem, ra, cl, lane);
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     kt += HFX_KEY_TILE;
     if (kt < it.ke) continue;
 
-    // hand-over: the item is finished; its successor's first tiles are already on their way
+    // hand-over: the item is finished; its successor's first tile is in buffer 0 and on its way
     const bool carry_on = ts.next_ok;
     prefill_store<D>(a, H, it, wr, w, Hq, wave, lane, stage);
     tickets_take(t, s_tk);
@@ -946,12 +961,16 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     nx = items[t.nxt < n_items ? t.nxt : t.cur];   // asked for here, first looked at behind the wait for Q
     set_ticket_points();
     wr = wave_rows<D>(it, wave, n);
+    wave_end = min(wr.wave_kend, it.ke);
     q_load<D>(w, a, it, wr, Hq, j);
     // Q is needed by the very next MFMA.  Waiting for it here, in so many words, also tells the
     // compiler that nothing is in flight when the tile loop is re-entered; left to itself it
     // carries the Q loads into the loop as pending and drains the queue down to them on every tile.
     HFX_WAIT_VMCNT(0);
     set_stream();
+    // the page ids for the tile after this item's first were asked for while the item after this one
+    // had no ticket yet, if this item is one tile long: asked for again, now that it has
+    if (!tn_known) tn = stream_pages(bt_all, ts, it.kb + HFX_KEY_TILE, gn, tn_known);
 #pragma unroll
     for (int b = 0; b < D / 32; ++b)
 #pragma unroll
@@ -959,10 +978,8 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     w.m = NEG_INF;
     w.l = 0.f;
     kt = it.kb;
-    recopy = kt + HFX_KEY_TILE >= it.ke;
   }
-  HFX_WAIT_VMCNT(0);   // copies and fragments requested past the end of the stream
-  __syncthreads();     // ... by every wavefront, before the LDS is used for anything else
+  __syncthreads();     // every wavefront is done with the stage buffers before the LDS is used for anything else
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -987,7 +1004,8 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   a.out = out;
   __shared__ __attribute__((aligned(1024))) char smem[Smem<D>::kBytes];
   __shared__ int s_tk[2];
-  __shared__ __attribute__((aligned(128))) char s_ostage[4 * 4096];   // result rows on their way out (prefill_store)
+  // result rows on their way out (prefill_store): at D = 128 they go through a free stage buffer
+  __shared__ __attribute__((aligned(128))) char s_ostage[D == 128 ? 128 : 4 * 4096];
   const HfxHeader* H = &hdr;
   const HfxItem* items = reinterpret_cast<const HfxItem*>(a.desc + H->off_items);
   const int n_items = H->n_items;
