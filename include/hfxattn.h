@@ -78,10 +78,12 @@ typedef struct {
  * (including NaN) and never influence a result.
  */
 
-/* Human-readable name of a status code.  Returns a static string. */
+/* Human-readable name of a status code (a utility of this interface; no passage of the paper behind
+ * it).  Returns a static string. */
 const char* hfx_status_string(hfx_status status);
 
-/* Library version.  Either pointer may be NULL. [host] */
+/* Library version: major, and the descriptor layout version as minor (utility; no passage of the
+ * paper behind it).  Either pointer may be NULL. [host] */
 hfx_status hfx_version(int32_t* major, int32_t* minor);
 
 /*
@@ -174,6 +176,16 @@ hfx_status hfx_fill_batch_desc(const hfx_shape* shape, int32_t num_requests,
  *   host_desc      [host]   the staging buffer hfx_build_batch_desc filled; only
  *                           its header is read (launch geometry), on the host
  *   device_desc    [device] descriptor uploaded by hfx_build_batch_desc
+ * Pairing rule: host_desc and device_desc must hold the SAME descriptor, the one
+ * written by one hfx_build_batch_desc (or hfx_fill_batch_desc plus the caller's
+ * own upload) call.  The launch takes its item, group, merge-unit and run counts
+ * and its table offsets from host_desc's header and walks device_desc with them;
+ * it cannot see whether the two match.  A caller that refills a staging buffer
+ * for the next step while an older device_desc is still being launched must
+ * keep one staging buffer per device descriptor (the header is read during the
+ * call itself, not later: once the call has returned host_desc may be reused).
+ * The same rule holds for hfx_mixed_paged_attention_static, hfx_gather_kv and
+ * hfx_append_kv.
  *   workspace      [device] device_workspace_bytes of scratch, 16-byte aligned;
  *                           contents need no initialisation; may be NULL when 0
  *

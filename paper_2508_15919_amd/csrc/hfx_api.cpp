@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/hfxattn.h"
@@ -27,24 +28,31 @@ hfx_status check_header(const hfx_shape* shape, const void* host_desc, HfxHeader
   return HFX_OK;
 }
 
-// resident workgroups of the persistent kernel on the current device, cached per device
+// Workgroups of the persistent launch on the current device: what fits on the chip at once (cached per
+// device), but never more than the width the planner laid the queue out for -- its first rounds deal
+// queue positions b and b + HFX_PLAN_WGS to workgroup b.
 hfx_status persistent_grid(int head_dim, int* grid) {
-  static int cache[64][2];
+  static std::mutex mu;
+  static int cache[HFX_MAX_DEVICES][2];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return HFX_ERR_DEVICE;
+  if (dev < 0 || dev >= HFX_MAX_DEVICES) return HFX_ERR_DEVICE;
   const int slot = head_dim == 128 ? 1 : 0;
-  if (dev >= 0 && dev < 64 && cache[dev][slot] > 0) {
-    *grid = cache[dev][slot];
-    return HFX_OK;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cache[dev][slot] == 0) {
+    int cus = 0, per_cu = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return HFX_ERR_DEVICE;
+    if (hfx::max_resident_workgroups(head_dim, &per_cu) != hipSuccess) return HFX_ERR_DEVICE;
+    if (cus < 1 || per_cu < 1) return HFX_ERR_DEVICE;
+    cache[dev][slot] = cus * per_cu < HFX_PLAN_WGS ? cus * per_cu : HFX_PLAN_WGS;
   }
-  int cus = 0, per_cu = 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return HFX_ERR_DEVICE;
-  if (hfx::max_resident_workgroups(head_dim, &per_cu) != hipSuccess) return HFX_ERR_DEVICE;
-  if (cus < 1 || per_cu < 1) return HFX_ERR_DEVICE;
-  *grid = cus * per_cu;
-  if (dev >= 0 && dev < 64) cache[dev][slot] = *grid;
+  *grid = cache[dev][slot];
   return HFX_OK;
 }
+
+}  // namespace
+
+namespace {
 
 // The attention call proper; `h` is the descriptor's header, already checked against the shape.
 hfx_status run_attention(const HfxHeader& h, const void* q, const void* kv_pool, void* device_desc, void* workspace,

@@ -242,6 +242,18 @@ def test_validation_errors(lib):
     assert lib.hfx_mixed_paged_attention(ctypes.byref(other), 16, 16, host.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_SHAPE
     # misaligned device pointer
     assert lib.hfx_mixed_paged_attention(ctypes.byref(shape), 8, 16, host.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_ALIGN
+    # the other calls that take their geometry from the staging buffer's header refuse the same blobs
+    sh, oth = ctypes.byref(shape), ctypes.byref(other)
+    assert lib.hfx_mixed_paged_attention_static(sh, 16, 16, junk.ctypes.data, 16, 16, None) == hb.HFX_ERR_DESC
+    assert lib.hfx_mixed_paged_attention_static(oth, 16, 16, host.ctypes.data, 16, 16, None) == hb.HFX_ERR_SHAPE
+    assert lib.hfx_gather_kv(sh, 16, junk.ctypes.data, 16, 0, 16, 16, None) == hb.HFX_ERR_DESC
+    assert lib.hfx_gather_kv(oth, 16, host.ctypes.data, 16, 0, 16, 16, None) == hb.HFX_ERR_SHAPE
+    assert lib.hfx_gather_kv(sh, 16, host.ctypes.data, 16, 4, 16, 16, None) == hb.HFX_ERR_LEN      # request out of range
+    assert lib.hfx_append_kv(sh, 16, 16, 16, junk.ctypes.data, 16, None) == hb.HFX_ERR_DESC
+    assert lib.hfx_append_kv(oth, 16, 16, 16, host.ctypes.data, 16, None) == hb.HFX_ERR_SHAPE
+    stale = host.copy()
+    stale[4] ^= 1                                         # a descriptor of another layout version
+    assert lib.hfx_mixed_paged_attention(sh, 16, 16, stale.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_DESC
 
 
 def test_extra_reserved_pages_are_ignored(lib):
