@@ -531,7 +531,7 @@ struct StagePages {     // the two pages of a 32-key stage
 // first and of the second page (1 KB per instruction, as it lies).
 struct CopyLane {
   unsigned src_off;    // byte offset of the lane's first piece inside the (page, kv-head) K|V block pair
-  unsigned lds_off;    // where the wavefront's pieces start inside a stage buffer
+  unsigned lds_off;    // where the lane's pieces start inside a stage buffer
   bool second;         // the lane reads the stage's second page
 };
 
@@ -543,11 +543,16 @@ __device__ __forceinline__ CopyLane copy_lane(int wave, int lane) {
     // lane l fills LDS slot l of a 1 KB group: slot = 32 * (dimension half) + key, so that the 16
     // lanes the LDS serves together later read 16 different bank groups
     c.src_off = (unsigned)(((kk0 * 16 + (lane & 15)) * 16 + (lane >> 5) * 8) * 2);
-    c.lds_off = (unsigned)(kk0 * 1024);
+    c.lds_off = (unsigned)(kk0 * 1024 + lane * 16);
     c.second = (lane >> 4) & 1;
   } else {
     c.src_off = (unsigned)(HFX_PAGE * D * 2 + lane * 16);
-    c.lds_off = (unsigned)(Smem<D>::kKBytes + (wave - 2) * Smem<D>::kPageVBytes);
+    // A lane holds one half (8 slots, 16 bytes) of one dimension's 32-byte V row; the halves of rows
+    // 8-15 and 24-31 of a 1 KB group change places in LDS, so that the 16 lanes the LDS serves together
+    // hit 16 different bank groups both when the pieces are written (8 rows, both halves) and when the
+    // MFMA fragments are read (16 rows, one half); laid out as in the pool the reads collide in pairs.
+    const int row = lane >> 1, half = lane & 1;
+    c.lds_off = (unsigned)(Smem<D>::kKBytes + (wave - 2) * Smem<D>::kPageVBytes + (2 * row + (half ^ ((row >> 3) & 1))) * 16);
     c.second = wave == 3;
   }
   return c;
@@ -579,7 +584,7 @@ __device__ __forceinline__ void stage_load(StageRegs<D>& sr, const __bf16* pool,
 // ... and puts them into the stage buffer `buf` (1 KB per instruction, lane l at 16 l).
 template <int D>
 __device__ __forceinline__ void stage_write(char* buf, const StageRegs<D>& sr, const CopyLane& cl, int lane) {
-  char* dst = buf + cl.lds_off + lane * 16;
+  char* dst = buf + cl.lds_off;
 #pragma unroll
   for (int i = 0; i < Smem<D>::kCopies; ++i) *reinterpret_cast<u32x4*>(dst + i * 1024) = sr.r[i];
 }
@@ -621,22 +626,21 @@ __device__ __forceinline__ void softmax_block(f32x16& s, PrefillWave<D>& w, bf16
     w.m = mn;
   }
   const float mneg = w.m == NEG_INF ? 0.f : -w.m;
-  // weights rounded to bf16 in pairs; their sum is taken over the rounded values (the ones the
-  // second contraction uses) with one dot-product instruction per pair
-  bf16x2 ones;
-  ones[0] = (__bf16)1.0f;
-  ones[1] = (__bf16)1.0f;
-  float ps = 0.f;
+  // The weights are summed in fp32 with plain adds, four partial sums.  (The two-element dot-product
+  // instruction would sum the rounded weights in half as many instructions, but it does not issue
+  // while a matrix instruction executes -- measured: 28 of them interleaved with 4 MFMA 32x32x16
+  // take the sum of both times, every other instruction of this function the maximum -- and so
+  // serialises the softmax of one wavefront with the MFMAs of both wavefronts of its SIMD.)
+  float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int v = 0; v < 16; v += 2) {
-    bf16x2 pk;
-    pk[0] = (__bf16)fast_exp2(__builtin_fmaf(s[v], sl2, mneg));
-    pk[1] = (__bf16)fast_exp2(__builtin_fmaf(s[v + 1], sl2, mneg));
-    ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
-    pb[v >> 3][v & 7] = pk[0];
-    pb[v >> 3][(v & 7) + 1] = pk[1];
+    const float p0 = fast_exp2(__builtin_fmaf(s[v], sl2, mneg));
+    const float p1 = fast_exp2(__builtin_fmaf(s[v + 1], sl2, mneg));
+    ps[(v >> 1) & 3] += p0 + p1;
+    pb[v >> 3][v & 7] = (__bf16)p0;
+    pb[v >> 3][(v & 7) + 1] = (__bf16)p1;
   }
-  w.l += ps;
+  w.l += (ps[0] + ps[1]) + (ps[2] + ps[3]);
 }
 
 // One 32-key stage out of the LDS buffer `buf` against the wavefront's 32 rows; key0 is the stage's
@@ -856,7 +860,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
   // row of this lane's key inside the stage's 32 keys
   const int krow = (n >> 4) * 16 + ((n >> 2) & 1) * 8 + ((n >> 3) & 1) * 4 + (n & 3);
   const int k_lane = (j * 32 + krow) * 16;
-  const int v_lane = (n * 2 + j) * 16;   // V^T rows 32b + n, keys 8j.. of a page: 16 bytes at (32b + n) * 32 + 16j
+  const int v_lane = (n * 2 + (j ^ ((n >> 3) & 1))) * 16;   // V^T rows 32b + n, keys 8j.. of a page, at their swizzled place (copy_lane)
   const CopyLane cl = copy_lane<D>(wave, lane);
 
   HfxItem it = items[t.cur];
