@@ -303,11 +303,11 @@ class DescHeader(ctypes.Structure):
                 ("total_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
                 ("ws_off_ml", ctypes.c_uint64), ("max_group_rows", ctypes.c_int32),
                 ("n_units", ctypes.c_int32), ("off_units", ctypes.c_uint32), ("n_runs", ctypes.c_int32),
-                ("off_runs", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 3)]
+                ("off_runs", ctypes.c_uint32), ("queue_classes", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 2)]
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in ("type", "req", "group", "slot_row", "h0", "hn", "row0", "nrows",
-                                               "kb", "ke", "cost", "pad", "rq_kind", "rq_q_len", "rq_ctx_len",
+                                               "kb", "ke", "cost", "home", "rq_kind", "rq_q_len", "rq_ctx_len",
                                                "rq_q_start", "rq_bt_start", "rq_n_pages", "rq_bt_len", "rq_pad1")])
 REQ_DTYPE = np.dtype([(n, np.int32) for n in ("kind", "q_len", "ctx_len", "q_start", "bt_start", "n_pages",
                                               "bt_len", "pad1")])

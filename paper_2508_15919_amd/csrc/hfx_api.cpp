@@ -64,6 +64,7 @@ hfx_status run_attention(const HfxHeader& h, const void* q, const void* kv_pool,
       (h.workspace_bytes > 0 && !aligned16(workspace)))
     return HFX_ERR_ALIGN;
   if (h.n_items < 1) return HFX_ERR_DESC;
+  if ((h.queue_classes != 1 && h.queue_classes != HFX_QUEUE_CLASSES) || h.n_ctrl <= HFX_QUEUE_CLASSES) return HFX_ERR_DESC;
   int grid = 0;
   st = persistent_grid(h.head_dim, &grid);
   if (st != HFX_OK) return st;

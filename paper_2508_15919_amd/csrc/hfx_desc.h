@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define HFX_DESC_MAGIC 0x31584648u /* "HFX1" */
-#define HFX_DESC_VERSION 14u
+#define HFX_DESC_VERSION 15u
 #define HFX_PAGE 16
 #define HFX_WG_THREADS 256
 #define HFX_PLAN_WGS 512         /* planning width: 256 compute units x 2 resident workgroups */
@@ -12,6 +12,7 @@
 #define HFX_STAGE_KEYS 32        /* keys per prefill pipeline stage (2 pages) */
 #define HFX_BT_PAD 16            /* stored block-table entries after a request's last page, all naming that page */
 #define HFX_WAVE_ROWS 32         /* query rows one wavefront owns in a prefill item (one MFMA row block) */
+#define HFX_QUEUE_CLASSES 8      /* queue positions p with equal p % 8 form a class: one per accelerator die (XCD), each with an L2 of its own */
 
 #define HFX_STATIC_WS_BYTES (64u << 20) /* fixed workspace of the entry point that allocates nothing */
 #define HFX_MAX_DEVICES 64
@@ -27,7 +28,8 @@ struct HfxHeader {
   int32_t n_partial_rows;       /* workspace rows: one (query row, q-head) partial each */
   int32_t n_bt;                 /* page ids stored */
   uint32_t off_ctrl, off_req, off_bt, off_items, off_groups;
-  uint32_t n_ctrl;              /* control words: [0] tickets handed out past the two dealt to each workgroup by index, [1] finished workgroups */
+  uint32_t n_ctrl;              /* control words: [c], c < queue_classes: tickets of class c handed out past the two dealt
+                                   to each workgroup by index; [HFX_QUEUE_CLASSES]: finished workgroups */
   uint64_t total_bytes;
   uint64_t workspace_bytes;
   uint64_t ws_off_ml;           /* byte offset of the (m, l) pairs inside the workspace; acc rows start at 0 */
@@ -36,7 +38,8 @@ struct HfxHeader {
   uint32_t off_units;
   int32_t n_runs;               /* append runs: the new tokens of the step, cut at page boundaries */
   uint32_t off_runs;
-  uint32_t reserved[3];
+  uint32_t queue_classes;       /* 1 or HFX_QUEUE_CLASSES: how many classes the queue positions past the dealt ones fall into */
+  uint32_t reserved[2];
 };
 
 struct HfxReq {
@@ -63,12 +66,14 @@ struct HfxRun {
 //           nrows = rows covered (32 * 4 / hn), kb/ke = key range in tokens (kb % 64 == 0).
 //  group >= 0: the item is one of several splits; its partial goes to workspace rows
 //           [slot_row, slot_row + rows) and the merge kernel combines the group afterwards.
+//  home   : the queue class (0 .. HFX_QUEUE_CLASSES-1) whose workgroups the planner meant the item
+//           for, or -1 where the queue order has no classes; planner bookkeeping, kernels ignore it.
 //  The request's record is repeated inside the item so that a workgroup needs one dependent load
 //  less between taking a ticket and issuing its first KV load.
 struct HfxItem {
   int32_t type, req, group, slot_row;
   int32_t h0, hn, row0, nrows;
-  int32_t kb, ke, cost, pad;
+  int32_t kb, ke, cost, home;
   HfxReq rq;
 };
 

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(HFX_WG_THREADS) void merge_kernel(const HfxUnit* __
 // time, and in a step with about three items per workgroup that left half the chip idle while
 // the other half worked through its reservations.  The first two tickets of a workgroup are its
 // index plus 0 and 1 grids (the queue is in descending cost, so this deals the largest items
-// out evenly, and a workgroup starts without a round trip to the counter).
+// out evenly, and a workgroup starts without a round trip to a counter).
 constexpr int kDealtTickets = 2;
 struct Tickets {
   int cur, nxt;
@@ -239,18 +239,51 @@ struct Tickets {
   int parity;
 };
 
-// Thread 0 asks the counter for one more ticket (when `ask`); the reply is first touched by
+// Queue positions past the dealt ones fall into `nc` classes (1 or HFX_QUEUE_CLASSES, the
+// planner's choice per step), position p into class p % nc, each with a counter of its own, and a
+// workgroup asks the counter of the class of its index.  Workgroups are placed on the chip's dies
+// round-robin by index, so with HFX_QUEUE_CLASSES classes a class is served by the workgroups of
+// one die, and the planner puts items that read the same keys into one class: they then share
+// that die's L2.
+//
+// Thread 0 asks its class's counter for one more ticket (when `ask`); the reply is first touched by
 // tickets_publish.  The other lanes, and a call with ask == false, set the field to zero rather
 // than keep what it held: keeping it reads the register the previous request wrote, and for that
 // the compiler puts a wait for everything in flight in front of this request.
-__device__ __forceinline__ void tickets_reserve(Tickets& t, int* ctrl, bool ask = true) {
+__device__ __forceinline__ void tickets_reserve(Tickets& t, int* ctrl, int nc, bool ask = true) {
   int r = 0;
-  if (ask && threadIdx.x == 0) r = atomicAdd(ctrl, 1);
+  if (ask && threadIdx.x == 0) r = atomicAdd(ctrl + ((int)blockIdx.x & (nc - 1)), 1);
   t.pending = r;
 }
-// thread 0 puts the reserved ticket into LDS (two slots alternate, so one barrier per hand-over is enough)
-__device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk) {
-  if (threadIdx.x == 0) s_tk[t.parity] = kDealtTickets * (int)gridDim.x + t.pending;
+// Thread 0 puts the reserved ticket into LDS (two slots alternate, so one barrier per hand-over is
+// enough).  A reply past the end of the queue means the workgroup's class is empty.  It then reads
+// all counters (one round trip) and asks the class that has most positions left for one, so
+// that a die that finishes early helps the others; when other workgroups got there first (the
+// reply is past the end again) it looks again, a few times.  Giving up early costs balance, not
+// correctness: every class is drained by its own workgroups whether or not others help.
+constexpr int kStealAttempts = 4;
+__device__ __forceinline__ void tickets_publish(const Tickets& t, int* s_tk, int* ctrl, int n_items, int nc) {
+  if (threadIdx.x == 0) {
+    const int base = kDealtTickets * (int)gridDim.x;
+    int pos = base + t.pending * nc + ((int)blockIdx.x & (nc - 1));
+    if (nc > 1) {
+      for (int attempt = 0; attempt < kStealAttempts && pos >= n_items; ++attempt) {
+        int best = 0, best_left = 0;
+        for (int k = 0; k < HFX_QUEUE_CLASSES; ++k) {
+          const int taken = __hip_atomic_load(ctrl + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          // positions base + r * classes + k below n_items with r >= taken
+          const int left = (n_items - base - k + HFX_QUEUE_CLASSES - 1) / HFX_QUEUE_CLASSES - taken;
+          if (left > best_left) {
+            best_left = left;
+            best = k;
+          }
+        }
+        if (best_left <= 0) break;
+        pos = base + atomicAdd(ctrl + best, 1) * HFX_QUEUE_CLASSES + best;
+      }
+    }
+    s_tk[t.parity] = pos;
+  }
 }
 // ... after a workgroup barrier that follows tickets_publish
 __device__ __forceinline__ void tickets_take(Tickets& t, int* s_tk) {
@@ -409,7 +442,7 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
     // page ids are fetched one pair ahead of the KV loads that need them
     while (pp < pe) {
       if (!reserved && pp + 4 * step >= pe) {   // a few pairs before the end (thread 0 sits in the first wavefront, which always has pairs)
-        tickets_reserve(t, ctrl);
+        tickets_reserve(t, ctrl, (int)H->queue_classes);
         reserved = true;
       }
       if (pp + step < pe) decode_load<D>(r1, a.pool, b0, b1, Hkv, g, k_sel, k_off, v_sel, v_off);
@@ -439,7 +472,7 @@ __device__ void decode_run(const KArgs& a, const HfxHeader* H, const HfxItem* __
     // The reply to the ticket request has come back in front of the last pairs' loads (returns
     // are in order), so publishing it here waits for nothing; after the requests below it would
     // wait for them.  The barriers of the epilogue stand between this write and its readers.
-    tickets_publish(t, s_tk);
+    tickets_publish(t, s_tk, ctrl, n_items, (int)H->queue_classes);
     // both register sets and the Q operand are free now: start on the next item
     if (carry_on) {
       if (dn.pp < dn.pe) decode_load<D>(r0, a.pool, dn.a0, dn.a1, Hkv, dn.g, k_sel, k_off, v_sel, v_off);
@@ -886,7 +919,7 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
     const int ip = n_tiles > 2 ? n_tiles - 2 : 0;
     publish_kt = it.kb + ip * HFX_KEY_TILE;
     reserve_kt = ip > 0 ? publish_kt - HFX_KEY_TILE : -1;
-    tickets_reserve(t, ctrl, ip == 0);   // the field is dead here: the last publish has read it
+    tickets_reserve(t, ctrl, (int)H->queue_classes, ip == 0);   // the field is dead here: the last publish has read it
   };
   set_ticket_points();
 
@@ -926,9 +959,9 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
       // The ticket asked for earlier is published ahead of this tile's barriers, so that the
       // hand-over at the end of the item needs no barrier of its own.  Reading the counter's reply
       // makes the wavefront wait for what it had in flight when it asked.
-      tickets_publish(t, s_tk);
+      tickets_publish(t, s_tk, ctrl, n_items, (int)H->queue_classes);
     }
-    if (kt == reserve_kt) tickets_reserve(t, ctrl);   // never in the publishing tile
+    if (kt == reserve_kt) tickets_reserve(t, ctrl, (int)H->queue_classes);   // never in the publishing tile
     // ---- first stage: keys kt .. kt + 31 out of buffer 0
     stage_load<D>(ra, a.pool, tn.half[0], Hkv, gn, cl, wave);
     if (kt < wave_end) {
@@ -988,8 +1021,8 @@ __device__ void prefill_run(const KArgs& a, const HfxHeader* H, const HfxItem* _
 
 // ----------------------------------------------------------------------------------------------
 // The persistent kernel: workgroups pull items in descending modelled cost until the queue is
-// empty.  A workgroup always knows its next item (see Tickets).  The queue head lives in the
-// descriptor; the last workgroup to leave restores it to zero so the descriptor can serve the
+// empty.  A workgroup always knows its next item (see Tickets).  The queue counters live in the
+// descriptor; the last workgroup to leave restores them to zero so the descriptor can serve the
 // next launch.
 // ----------------------------------------------------------------------------------------------
 template <int D>
@@ -1030,10 +1063,9 @@ __global__ __launch_bounds__(HFX_WG_THREADS, 2) void mixed_attention_kernel(
   HFX_WAIT_VMCNT(0);
   asm volatile("" ::: "memory");
   if (threadIdx.x == 0) {
-    const int done = atomicAdd(&ctrl[1], 1);
+    const int done = atomicAdd(&ctrl[HFX_QUEUE_CLASSES], 1);
     if (done == (int)gridDim.x - 1) {
-      atomicExch(&ctrl[0], 0);
-      atomicExch(&ctrl[1], 0);
+      for (int c = 0; c <= HFX_QUEUE_CLASSES; ++c) atomicExch(&ctrl[c], 0);
     }
   }
 }

@@ -20,7 +20,18 @@ static const int kMinDecodeTokens = 128;
 static const int kMinPrefillKeys = 256;
 static const int kMaxSplits = 64;
 static const int kDecodeItemsPerWg = 4;    // decode partials are small (rows of D + 2 floats per q-head)
+// Which prefill-dominated steps get a queue per die (see the queue order in plan_step), by items per
+// workgroup of the planning width.  Steps of many short items gain nothing from it (their time
+// goes into item hand-overs, not into key traffic).  In the first rounds all workgroups of a die
+// start together, and those that read the same keys then move in step: every cache line is a
+// first touch for all of them at once, its full memory latency shows in each, and a tile takes up
+// to twice as long as when neighbours run a little ahead and leave the lines in the L2.  Later
+// rounds start staggered.  Steps of fewer than three rounds therefore keep the plain order.
+static const int kClassRoundsMin = 3;
+static const int kClassRoundsMax = 8;
+static const int kFitRounds = 6;           // steps with fewer rounds of prefill items than this get whole rounds
 static const int kPrefillItemsPerWg = 2;   // prefill partials are 128 rows: split only where balance needs it
+static const uint32_t kNoUnit = 0x0fffffffu;   // items that share keys with no other item
 
 static int kv_heads_per_item(int Hkv) { return (Hkv % 4 == 0) ? 4 : (Hkv % 2 == 0 ? 2 : 1); }
 static int q_heads_per_item(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1); }
@@ -49,6 +60,21 @@ static int64_t pairs_in(int64_t p, int64_t r0, int64_t r1, int64_t kb, int64_t k
   return n * (p + 1 - kb) + (i_lo + i_hi - 1) * n / 2 + (r1 - i_hi) * (ke - kb);
 }
 
+// How the keys a row tile (chunk rows [r0, r1) behind p earlier tokens) sees are cut into items
+// of at most about cap_ns each: nsplit pieces of tiles_per key tiles (the last may be shorter).
+static void prefill_splits(int64_t p, int64_t r0, int64_t r1, int D, int hpw, double cap_ns, int64_t* nsplit_out,
+                           int64_t* tiles_per_out) {
+  const int64_t kmax = p + r1;
+  const int64_t ntiles = (kmax + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
+  const double ns_all = 4.0 * D * hpw * (double)pairs_in(p, r0, r1, 0, kmax) / kPrefillFlopsPerNs;
+  int64_t nsplit = (int64_t)std::ceil(ns_all / cap_ns);
+  nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kMaxSplits));
+  int64_t tiles_per = (ntiles + nsplit - 1) / nsplit;
+  tiles_per = std::max<int64_t>(tiles_per, kMinPrefillKeys / HFX_KEY_TILE);
+  *nsplit_out = (ntiles + tiles_per - 1) / tiles_per;
+  *tiles_per_out = tiles_per;
+}
+
 static int32_t clamp_cost(double ns) {
   if (ns < 1.0) return 1;
   if (ns > 2.0e9) return 2000000000;
@@ -68,6 +94,8 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   P.reqs.assign((size_t)R, HfxReq());
   P.items.clear();
   P.groups.clear();
+  P.item_unit.clear();
+  P.item_frac.clear();
   int64_t T = 0, nbt = 0;
   double dec_ns = 0.0, pre_ns = 0.0;   // modelled time of each kind of work
   for (int r = 0; r < R; ++r) {
@@ -114,11 +142,46 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
   // at 0.75, unsplit there, the longest item starts to decide the step).
   if (dec_ns > pre_ns) cap_prefill_ns = std::max(cap_prefill_ns, 0.6 * total_ns / HFX_PLAN_WGS);
 
-  int64_t rows = 0;
-  std::vector<int32_t>& split_cost = P.split_cost;
   const int ngc = kv_heads_per_item(Hkv);
   const int hpw = q_heads_per_item(G);
   const int rows_wg = HFX_WAVE_ROWS * (4 / hpw);
+  // A prefill-dominated step of few, about equally expensive items per workgroup lasts a whole
+  // number of items: 2.25 items per workgroup take as long as 3.  Where the cut above leaves a
+  // partly filled last round, the cap is raised (by up to a half) to the smallest value at which
+  // the prefill items fill whole rounds of the planning width.
+  if (pre_ns > dec_ns) {
+    auto count_items = [&](double cap) {
+      int64_t count = 0;
+      for (int r = 0; r < R; ++r) {
+        if (kind[r] != HFX_PREFILL) continue;
+        const int64_t p = ctx_len[r] - q_len[r];
+        const int n_rt = (q_len[r] + rows_wg - 1) / rows_wg;
+        for (int rt = 0; rt < n_rt; ++rt) {
+          const int64_t r0 = (int64_t)rt * rows_wg, r1 = std::min<int64_t>(q_len[r], r0 + rows_wg);
+          int64_t nsplit, tiles_per;
+          prefill_splits(p, r0, r1, D, hpw, cap, &nsplit, &tiles_per);
+          count += nsplit * Hkv * (G / hpw);
+        }
+      }
+      return count;
+    };
+    const int64_t n0 = count_items(cap_prefill_ns);
+    const int64_t whole = n0 / HFX_PLAN_WGS * HFX_PLAN_WGS;
+    if (whole >= HFX_PLAN_WGS && n0 > whole && n0 < (int64_t)kFitRounds * HFX_PLAN_WGS) {
+      double lo = cap_prefill_ns, hi = 1.5 * cap_prefill_ns;   // count(lo) > whole; is count(hi) <= whole?
+      if (count_items(hi) <= whole) {
+        for (int it = 0; it < 12; ++it) {
+          const double mid = 0.5 * (lo + hi);
+          (count_items(mid) <= whole ? hi : lo) = mid;
+        }
+        cap_prefill_ns = hi;
+      }
+    }
+  }
+
+  int64_t rows = 0;
+  std::vector<int32_t>& split_cost = P.split_cost;
+  int64_t pre_ord = 0;              // prefill requests seen so far
   for (int r = 0; r < R; ++r) {
     const HfxReq& q = P.reqs[(size_t)r];
     if (q.kind == HFX_DECODE) {
@@ -155,7 +218,10 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
           it.ke = (int32_t)std::min<int64_t>(q.n_pages, (int64_t)(s + 1) * pages_per);
           int64_t toks = std::min<int64_t>(q.ctx_len, (int64_t)it.ke * HFX_PAGE) - (int64_t)it.kb * HFX_PAGE;
           it.cost = clamp_cost((double)toks * ns_per_token + 2000.0);
+          it.home = -1;
           P.items.push_back(it);
+          P.item_unit.push_back(kNoUnit);
+          P.item_frac.push_back(0.f);
         }
         if (nsplit > 1) rows += (int64_t)nsplit * ngc * G;
       }
@@ -165,13 +231,8 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       for (int rt = 0; rt < n_rt; ++rt) {
         const int64_t r0 = (int64_t)rt * rows_wg, r1 = std::min<int64_t>(q.q_len, r0 + rows_wg);
         const int64_t kmax = p + r1;
-        const int64_t ntiles = (kmax + HFX_KEY_TILE - 1) / HFX_KEY_TILE;
-        const double ns_all = 4.0 * D * hpw * (double)pairs_in(p, r0, r1, 0, kmax) / kPrefillFlopsPerNs;
-        int64_t nsplit = (int64_t)std::ceil(ns_all / cap_prefill_ns);
-        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kMaxSplits));
-        int64_t tiles_per = (ntiles + nsplit - 1) / nsplit;
-        tiles_per = std::max<int64_t>(tiles_per, kMinPrefillKeys / HFX_KEY_TILE);
-        nsplit = (ntiles + tiles_per - 1) / tiles_per;
+        int64_t nsplit, tiles_per;
+        prefill_splits(p, r0, r1, D, hpw, cap_prefill_ns, &nsplit, &tiles_per);
         split_cost.resize((size_t)nsplit);
         for (int64_t s = 0; s < nsplit; ++s) {
           const int64_t kb = s * tiles_per * HFX_KEY_TILE, ke = std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
@@ -201,11 +262,17 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
               it.kb = (int32_t)(s * tiles_per * HFX_KEY_TILE);
               it.ke = (int32_t)std::min<int64_t>(kmax, (s + 1) * tiles_per * HFX_KEY_TILE);
               it.cost = split_cost[(size_t)s];
+              it.home = -1;
               P.items.push_back(it);
+              // the row tiles and head blocks that read the s-th piece of the keys of (request, kv-head)
+              const int64_t unit = (pre_ord * Hkv + g) * kMaxSplits + s;
+              P.item_unit.push_back(unit < (int64_t)kNoUnit ? (uint32_t)unit : kNoUnit);
+              P.item_frac.push_back((float)rt / (float)n_rt);
             }
             if (nsplit > 1) rows += nsplit * 4 * HFX_WAVE_ROWS;
           }
       }
+      ++pre_ord;
     }
     if (rows > 0x7fffffff / 2 || P.items.size() > 0x3fffffffu) return HFX_ERR_LEN;
   }
@@ -243,6 +310,7 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
     // the queue order is kept as a permutation; the records are put in that order when the blob is written
     std::vector<uint32_t>& order = P.order;
     order.resize(n);
+    P.queue_classes = 1;
     if (dec_ns > pre_ns && pre_ns > 0.0) {
       // A step whose decode work outweighs its prefill work.  The first two items of workgroup b
       // are queue positions b and b + HFX_PLAN_WGS, and workgroups b and b + HFX_PLAN_WGS/2 share a
@@ -276,6 +344,103 @@ hfx_status plan_step(const hfx_shape* shape, int32_t R, const int32_t* kind, con
       while (di < dec.size() || pi < pre.size()) {
         for (size_t k = 0; k < kBlockItems && di < dec.size(); ++k) order[o++] = dec[di++];
         for (size_t k = 0; k < kBlockItems && pi < pre.size(); ++k) order[o++] = pre[pi++];
+      }
+    } else if (pre_ns > 0.0 && n >= (size_t)kClassRoundsMin * HFX_PLAN_WGS && n <= (size_t)kClassRoundsMax * HFX_PLAN_WGS &&
+               pre_ord * Hkv * kMaxSplits < (int64_t)kNoUnit) {
+      // A step whose prefill work outweighs its decode work.  Many prefill items read the same
+      // keys: all row tiles (and q-head blocks) of one request and kv-head that hold the same
+      // piece of the key range.  Call that set a unit.  The chip has HFX_QUEUE_CLASSES dies, each
+      // with an L2 of its own, and workgroup b runs on die b % HFX_QUEUE_CLASSES; the kernel hands
+      // queue position p to a workgroup of die p % HFX_QUEUE_CLASSES (as long as that die has work).
+      // So the queue is built per class: every unit gets a home class (largest total cost first,
+      // each to the class with the least cost so far), a class lists the items homed there in
+      // descending cost, and the classes are interleaved position by position.  Items of a unit
+      // that cost about the same then run side by side on one die and fetch their keys from
+      // memory once instead of once per die and round, while the queue as a whole still goes
+      // from the most to the least expensive items.  A decode item is a unit of its own.  When
+      // a class runs out of items before the others, its positions are filled from the tail of
+      // the class that has most left.
+      const size_t n_slots = (size_t)(pre_ord * Hkv * kMaxSplits);
+      std::vector<int64_t>& ucost = P.unit_cost;
+      std::vector<uint32_t>& ufill = P.unit_fill;
+      std::vector<uint32_t>& ustart = P.unit_start;
+      std::vector<uint64_t>& ukeys = P.unit_keys;
+      // A unit that would be a large share of a class's work is cut into sub-units of consecutive
+      // row tiles, each at most about half of one class's share of the step, so that there is
+      // something to balance with (a long prompt on one kv-head has as few units as it has splits).
+      ucost.assign(n_slots, 0);
+      int64_t all_cost = 0;
+      for (size_t i = 0; i < n; ++i) {
+        all_cost += P.items[i].cost;
+        if (P.item_unit[i] != kNoUnit) ucost[P.item_unit[i]] += P.items[i].cost;
+      }
+      const int64_t sub_cost = std::max<int64_t>(1, all_cost / (2 * HFX_QUEUE_CLASSES));
+      ufill.assign(n_slots, 0);     // sub-units of the slot
+      ustart.assign(n_slots, 0);    // index of its first sub-unit
+      size_t n_units = 0;
+      for (size_t u = 0; u < n_slots; ++u)
+        if (ucost[u] > 0) {
+          ufill[u] = (uint32_t)std::min<int64_t>((ucost[u] + sub_cost - 1) / sub_cost, 4 * HFX_QUEUE_CLASSES);
+          ustart[u] = (uint32_t)n_units;
+          n_units += ufill[u];
+        }
+      // decode items (and anything else without a unit) get singleton units behind those
+      for (size_t i = 0; i < n; ++i) {
+        const uint32_t u = P.item_unit[i];
+        if (u == kNoUnit) P.item_unit[i] = (uint32_t)n_units++;
+        else P.item_unit[i] = ustart[u] + std::min<uint32_t>(ufill[u] - 1, (uint32_t)(P.item_frac[i] * (float)ufill[u]));
+      }
+      ucost.assign(n_units, 0);     // total cost of the unit; once it has a home, the home
+      ustart.assign(n_units, 0);    // items in the unit
+      for (size_t i = 0; i < n; ++i) {
+        const uint32_t u = P.item_unit[i];
+        ucost[u] += P.items[i].cost;
+        ustart[u]++;
+      }
+      // home classes: units by descending total cost (36 bits of it, saturating; the low 28 bits
+      // of a key hold the unit's index)
+      ukeys.clear();
+      const int64_t kCostTop = (1ll << 36) - 1;
+      for (size_t u = 0; u < n_units; ++u)
+        if (ustart[u]) ukeys.push_back(((uint64_t)(kCostTop - std::min(ucost[u], kCostTop)) << 28) | (uint64_t)u);
+      std::sort(ukeys.begin(), ukeys.end());
+      int64_t load[HFX_QUEUE_CLASSES] = {0};
+      for (uint64_t& k : ukeys) {
+        const uint32_t u = (uint32_t)(k & 0x0fffffffu);
+        int home = 0;
+        for (int c = 1; c < HFX_QUEUE_CLASSES; ++c)
+          if (load[c] < load[home]) home = c;
+        load[home] += ucost[u];
+        ucost[u] = home;
+      }
+      // The items are in descending cost (a[]); a class's list is those of them that are homed
+      // there, in that order (a stable counting sort by class into b[]).
+      size_t head[HFX_QUEUE_CLASSES], tail[HFX_QUEUE_CLASSES];
+      for (int c = 0; c < HFX_QUEUE_CLASSES; ++c) tail[c] = 0;
+      for (size_t i = 0; i < n; ++i) {
+        const uint32_t idx = (uint32_t)(a[i] & 0xffffffffu);
+        const int home = (int)ucost[P.item_unit[idx]];
+        P.items[idx].home = home;
+        tail[home]++;
+      }
+      for (int c = 0, at = 0; c < HFX_QUEUE_CLASSES; ++c) {
+        head[c] = (size_t)at;
+        at += (int)tail[c];
+        tail[c] = head[c];          // fill cursor; ends up one past the class's last item
+      }
+      for (size_t i = 0; i < n; ++i) b[tail[P.items[(uint32_t)(a[i] & 0xffffffffu)].home]++] = a[i];
+      std::swap(a, b);
+      P.queue_classes = HFX_QUEUE_CLASSES;
+      for (size_t o = 0; o < n; ++o) {
+        const int c = (int)(o % HFX_QUEUE_CLASSES);
+        if (head[c] < tail[c]) {
+          order[o] = (uint32_t)(a[head[c]++] & 0xffffffffu);
+        } else {
+          int from = 0;
+          for (int y = 1; y < HFX_QUEUE_CLASSES; ++y)
+            if (tail[y] - head[y] > tail[from] - head[from]) from = y;
+          order[o] = (uint32_t)(a[--tail[from]] & 0xffffffffu);
+        }
       }
     } else {
       for (size_t i = 0; i < n; ++i) order[i] = (uint32_t)(a[i] & 0xffffffffu);
@@ -317,6 +482,7 @@ void layout_blob(const hfx_shape* shape, const Plan& P, HfxHeader* h) {
   h->n_partial_rows = P.n_partial_rows;
   h->n_bt = P.n_bt;
   h->n_ctrl = 16;
+  h->queue_classes = (uint32_t)P.queue_classes;
   h->max_group_rows = 0;
   for (const HfxGroup& g : P.groups) h->max_group_rows = std::max(h->max_group_rows, g.rows_per_split);
   uint64_t off = align_up(sizeof(HfxHeader), 256);

@@ -54,34 +54,80 @@ def lengths_only(Hq, Hkv, D, kind, q_len, ctx_len):
                            np.zeros((int(q_len.sum()), Hq, D), np.uint16), np.zeros((1, Hkv, 2, 16 * D), np.uint16))
 
 
+def check_class_order(b, items):
+    """Queue of a prefill-dominated step: 8 position classes (position mod 8), one per die.
+
+    The prefill items that read the same piece of the keys of one (request, kv-head), i.e. the same
+    split index over row tiles and head blocks, form a unit; the planner may cut a unit into sub-units
+    of consecutive row tiles.  A decode item is a unit of its own.  Checked here: the items of one
+    (unit, row tile) share a home class; class loads differ by no more than the largest total a unit
+    has in one class; the list of a class (its own items in position order, then what other classes
+    took off its tail) is in descending cost; a class's positions hold foreign items only behind its
+    own."""
+    G = b.num_q_heads // b.num_kv_heads
+    n = len(items)
+    cost, home_of = items["cost"].astype(np.int64), items["home"]
+    unit = {}
+    by_tile = {}
+    for i, it in enumerate(items):
+        if it["type"] == 1:
+            by_tile.setdefault((int(it["req"]), int(it["row0"]), int(it["h0"])), []).append((int(it["kb"]), i))
+        else:
+            unit[i] = ("d", i)
+    for (req, row0, h0), lst in by_tile.items():
+        for s, (_, i) in enumerate(sorted(lst)):
+            unit[i] = ("p", req, h0 // G, s)
+    home = {}
+    for i, it in enumerate(items):
+        assert 0 <= int(home_of[i]) < 8
+        k = unit[i] + (int(it["row0"]),)
+        assert home.setdefault(k, int(home_of[i])) == int(home_of[i]), "one home per unit and row tile"
+    loads, unit_total = [], {}
+    for c in range(8):
+        seq = list(range(c, n, 8))
+        own = [i for i in seq if int(home_of[i]) == c]
+        assert seq[:len(own)] == own, "foreign items only behind the class's own"
+        taken = [i for i in range(n) if int(home_of[i]) == c and i % 8 != c]
+        full = own + taken[::-1]                    # taken off the tail, last first
+        loads.append(int(cost[full].sum()))
+        assert np.all(np.diff(cost[full]) <= 0), "a class's list is in descending cost"
+        for i in full:
+            unit_total[(c, unit[i])] = unit_total.get((c, unit[i]), 0) + int(cost[i])
+    assert max(loads) - min(loads) <= max(unit_total.values()), (loads, max(unit_total.values()))
+
+
 def check_coverage(b, d):
     h, items, reqs, groups = d["header"], d["items"], d["reqs"], d["groups"]
     Hq, Hkv = b.num_q_heads, b.num_kv_heads
     G = Hq // Hkv
     assert h.n_items == len(items) == h.n_decode_items + h.n_prefill_items
-    for ty in (0, 1):
-        assert np.all(np.diff(items["cost"][items["type"] == ty]) <= 0), "each kind in descending modelled cost"
-    pre_first = np.nonzero(items["type"] == 1)[0]
-    if len(pre_first) == 0 or len(pre_first) == len(items) or np.all(np.diff(items["cost"]) <= 0):
-        pass                                   # one kind only, or plain descending order
+    ty = items["type"]
+    n_dec, n_pre = int((ty == 0).sum()), int((ty == 1).sum())
+    if np.all(items["home"] >= 0):
+        assert h.queue_classes == 8
+        check_class_order(b, items)
     else:
-        # decode-dominated mixed step: over the first two rounds of 512 positions the prefill items sit
-        # at the positions of the workgroups of the first ceil(n_pre / 4) CUs (position mod 256), at
-        # most 128 of them; behind that, blocks of 256, decode first, as long as both kinds last
-        ty = items["type"]
-        n_dec, n_pre = int((ty == 0).sum()), int((ty == 1).sum())
-        pair_cus = min((n_pre + 3) // 4, 128)
-        want = []
-        for pos in range(min(1024, n_dec + n_pre)):
-            slot = (pos % 512) % 256 < pair_cus
-            if (slot and n_pre) or not n_dec:
-                want.append(1); n_pre -= 1
-            else:
-                want.append(0); n_dec -= 1
-        while n_dec or n_pre:
-            k = min(256, n_dec); want += [0] * k; n_dec -= k
-            k = min(256, n_pre); want += [1] * k; n_pre -= k
-        assert ty.tolist() == want
+        assert np.all(items["home"] == -1) and h.queue_classes == 1
+        for k in (0, 1):
+            assert np.all(np.diff(items["cost"][ty == k]) <= 0), "each kind in descending modelled cost"
+        if n_pre == 0 or n_dec == 0 or np.all(np.diff(items["cost"]) <= 0):
+            pass                                   # one kind only, or plain descending order
+        else:
+            # decode-dominated mixed step: over the first two rounds of 512 positions the prefill items sit
+            # at the positions of the workgroups of the first ceil(n_pre / 4) CUs (position mod 256), at
+            # most 128 of them; behind that, blocks of 256, decode first, as long as both kinds last
+            pair_cus = min((n_pre + 3) // 4, 128)
+            want = []
+            for pos in range(min(1024, n_dec + n_pre)):
+                slot = (pos % 512) % 256 < pair_cus
+                if (slot and n_pre) or not n_dec:
+                    want.append(1); n_pre -= 1
+                else:
+                    want.append(0); n_dec -= 1
+            while n_dec or n_pre:
+                k = min(256, n_dec); want += [0] * k; n_dec -= k
+                k = min(256, n_pre); want += [1] * k; n_pre -= k
+            assert ty.tolist() == want
     assert np.all(d["ctrl"] == 0)
     # stored block table: exactly the needed pages, in order
     for r in range(b.num_requests):
@@ -181,6 +227,35 @@ def test_planner_covers_full_size_lengths(lib):
     assert d["groups"]["nsplit"].max() <= 64
 
 
+def test_queue_per_die_and_whole_rounds(lib):
+    """Prefill-dominated steps of three to eight items per workgroup get one queue class per die;
+    steps of few prefill items per workgroup are cut so that the prefill items fill whole rounds of 512."""
+    # four prompts' chunks of 2048 tokens at different depths plus 32 decodes (the prefill-heavy mixed shape)
+    g = np.random.default_rng(1)
+    dec = g.integers(512, 4097, 32).tolist()
+    b = lengths_only(32, 8, 128, [PREFILL] * 4 + [DECODE] * 32, [2048] * 4 + [1] * 32,
+                     [2048, 6144, 10240, 14336] + dec)
+    d = fill(b)
+    assert d["header"].queue_classes == 8 and 3 * 512 <= d["header"].n_items <= 8 * 512
+    check_coverage(b, d)
+    # one long prompt on one kv-head, with and without decodes beside it
+    b = lengths_only(8, 1, 128, [PREFILL] + [DECODE] * 16, [4096] + [1] * 16, [65536] + [90000] * 16)
+    d = fill(b)
+    assert d["header"].queue_classes == 8
+    check_coverage(b, d)
+    b = lengths_only(8, 1, 128, [PREFILL], [4096], [65536])
+    d = fill(b)
+    assert d["header"].n_prefill_items == 1024 and d["header"].queue_classes == 1
+    check_coverage(b, d)
+    # many short prompts, a decode-only step and a small step keep the single queue
+    b = lengths_only(32, 8, 128, [PREFILL] * 256, [256] * 256, [256] * 256)
+    assert fill(b)["header"].queue_classes == 1
+    b = lengths_only(32, 8, 128, [DECODE] * 64, [1] * 64, [4096] * 64)
+    assert fill(b)["header"].queue_classes == 1
+    b = lengths_only(32, 8, 128, [PREFILL] * 2, [512] * 2, [512, 2048])
+    assert fill(b)["header"].queue_classes == 1
+
+
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 64), (2, 2, 128), (16, 1, 64), (12, 4, 128), (6, 2, 64)])
 def test_planner_head_layouts_and_ragged_chunks(lib, Hq, Hkv, D):
     b = lengths_only(Hq, Hkv, D, [PREFILL, DECODE, PREFILL, DECODE, PREFILL], [1, 1, 33, 1, 130],
@@ -254,6 +329,12 @@ def test_validation_errors(lib):
     stale = host.copy()
     stale[4] ^= 1                                         # a descriptor of another layout version
     assert lib.hfx_mixed_paged_attention(sh, 16, 16, stale.ctypes.data, 16, None, 0, 16, None) == hb.HFX_ERR_DESC
+    # a header whose count of queue classes is neither 1 nor 8 (the kernel would index the counters with it)
+    bent = host.copy()
+    off = hb.DescHeader.queue_classes.offset
+    bent[off:off + 4] = np.frombuffer(np.uint32(5).tobytes(), np.uint8)
+    ws = 16 if hb.parse_desc(host)["header"].workspace_bytes else None
+    assert lib.hfx_mixed_paged_attention(sh, 16, 16, bent.ctypes.data, 16, ws, 1 << 40, 16, None) == hb.HFX_ERR_DESC
 
 
 def test_extra_reserved_pages_are_ignored(lib):
