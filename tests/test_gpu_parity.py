@@ -129,6 +129,27 @@ def test_descriptor_serves_repeated_launches(hb):
     assert d["header"].n_groups > 0
 
 
+def test_queue_per_die_step_and_repeated_launches(hb, oracle):
+    """A prefill-dominated step of four items per workgroup: the planner lays the queue out in one class
+    per die and the kernel keeps a ticket counter per class.  Compared with the oracle, launched again on
+    the same descriptor (all counters must have been put back), and with a decode request beside it."""
+    import torch
+    kinds = [PREFILL] * 4 + [DECODE] * 6
+    ql = [2048, 2048, 2048, 2000] + [1] * 6
+    cl = [2048, 2304, 2560, 2100] + [700, 33, 1500, 257, 4096, 16]
+    b = synth.make_batch(32, 8, 128, kinds, ql, cl, 4242)
+    step, _ = check_full(hb, oracle, b)
+    d = hb.parse_desc(step.host_desc.numpy())
+    assert d["header"].queue_classes == 8 and np.all(d["items"]["home"] >= 0)
+    first = step.out_bits().copy()
+    for _ in range(3):
+        step.out.zero_()
+        step.run()
+        assert np.array_equal(step.out_bits(), first)
+    torch.cuda.synchronize()
+    assert np.all(hb.parse_desc(step.device_desc.cpu().numpy())["ctrl"] == 0), "control words must be restored to zero"
+
+
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 64), (2, 2, 128), (16, 1, 64), (16, 1, 128), (12, 4, 128), (8, 8, 128),
                                       (6, 2, 64)])
 def test_head_layouts_and_ragged_lengths(hb, oracle, Hq, Hkv, D):
